@@ -1,0 +1,161 @@
+"""Parity of the HIP attention kernels with the CPU oracle, through the C ABI.
+
+Sizes span several 64-key tiles, several 4-block workgroups, ragged mask edges
+(window and sink sizes that are not multiples of 64) and the degenerate cases.
+Bar: 2e-2 max-abs, 5e-3 mean-abs on bf16 outputs (tests/helpers.py).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import minference_oracle as O
+from tests.helpers import assert_close_rows, random_qkv, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2407_02490_amd import binding
+    binding.lib()
+    return binding
+
+
+def run_heads(fn, q, k, v, heads, *args):
+    o = torch.full_like(q, float("nan"))
+    fn(q, k, v, o, heads, *args)
+    torch.cuda.synchronize()
+    return o
+
+
+@pytest.mark.parametrize("N,nq,nkv", [(64, 1, 1), (320, 2, 1), (1024, 4, 2)])
+def test_dense_matches_oracle(B, N, nq, nkv):
+    q, k, v = random_qkv(1, nq, nkv, N)
+    o = run_heads(B.minf_dense_attn, q, k, v, list(range(nq)))
+    g = nq // nkv
+    for h in range(nq):
+        want = O.dense_attention(to_f64(q[h]), to_f64(k[h // g]), to_f64(v[h // g]))
+        assert_close_rows(o[h], want, f"dense N={N} head {h}")
+
+
+@pytest.mark.parametrize("n_init,n_local", [(64, 128), (100, 200), (0, 65), (5, 1), (1024, 4096), (130, 64)])
+def test_ashape_matches_oracle(B, n_init, n_local):
+    N, nq, nkv = 1344, 4, 2          # 21 blocks: last workgroup has one idle wave slot
+    q, k, v = random_qkv(2, nq, nkv, N)
+    heads = [3, 0, 2]
+    o = run_heads(B.minf_ashape_attn, q, k, v, heads, n_init, n_local)
+    for h in heads:
+        want = O.ashape_attention(to_f64(q[h]), to_f64(k[h // 2]), to_f64(v[h // 2]), n_init, n_local)
+        assert_close_rows(o[h], want, f"ashape ({n_init},{n_local}) head {h}")
+    assert torch.isnan(o[1].float()).all()       # heads not listed are left untouched
+
+
+def test_ashape_strided_views_and_scale(B):
+    # q/k/v as slices of a fused [N, H, d] projection output (token-major)
+    N, nq, nkv = 512, 4, 4
+    g = torch.Generator().manual_seed(5)
+    fused = torch.randn(N, 3 * nq, 128, generator=g).to(torch.bfloat16).cuda()
+    q = fused[:, 0:nq].transpose(0, 1)
+    k = fused[:, nq:2 * nq].transpose(0, 1)
+    v = fused[:, 2 * nq:].transpose(0, 1)
+    o = torch.zeros(nq, N, 128, dtype=torch.bfloat16, device="cuda")
+    B.minf_ashape_attn(q, k, v, o, [1, 2], 64, 128, scale=0.05)
+    torch.cuda.synchronize()
+    for h in (1, 2):
+        want = O.ashape_attention(to_f64(q[h]), to_f64(k[h]), to_f64(v[h]), 64, 128, scale=0.05)
+        assert_close_rows(o[h], want, f"strided head {h}")
+
+
+def random_bs_index(rng, NB, topk, dense_diag=True):
+    idx = -np.ones((NB, topk), np.int64)
+    cnt = np.zeros(NB, np.int64)
+    for b in range(NB):
+        c = min(topk, b + 1)
+        sel = np.sort(rng.choice(b + 1, c, replace=False))
+        idx[b, :c], cnt[b] = sel, c
+    return idx, cnt
+
+
+def test_bs_matches_oracle(B, rng):
+    N, nq, nkv, topk = 1024, 4, 2, 5
+    NB = N // 64
+    q, k, v = random_qkv(3, nq, nkv, N)
+    heads = [0, 3]
+    idxs = [random_bs_index(rng, NB, topk) for _ in heads]
+    dev = B.bs_index_from_host(np.stack([i for i, _ in idxs]), np.stack([c for _, c in idxs]))
+    o = run_heads(B.minf_bs_attn, q, k, v, heads, dev)
+    for r, h in enumerate(heads):
+        want = O.bs_attention(to_f64(q[h]), to_f64(k[h // 2]), to_f64(v[h // 2]), idxs[r][0], idxs[r][1])
+        assert_close_rows(o[h], want, f"bs head {h}")
+
+
+def test_bs_full_index_is_dense(B):
+    N = 512
+    NB = N // 64
+    q, k, v = random_qkv(4, 1, 1, N)
+    idx = np.tile(np.arange(NB), (NB, 1))
+    cnt = np.arange(1, NB + 1)
+    idx = np.where(idx < cnt[:, None], idx, -1)
+    dev = B.bs_index_from_host(idx[None], cnt[None])
+    o = run_heads(B.minf_bs_attn, q, k, v, [0], dev)
+    assert_close_rows(o[0], O.dense_attention(to_f64(q[0]), to_f64(k[0]), to_f64(v[0])), "bs dense limit")
+
+
+def test_bs_ignores_bad_block_ids(B):
+    N = 256
+    q, k, v = random_qkv(6, 1, 1, N)
+    idx = np.array([[[0, -1, 99], [0, 1, 4], [7, 1, 2], [0, 3, -5]]])
+    cnt = np.array([[3, 3, 3, 3]])
+    dev = B.bs_index_from_host(idx, cnt)
+    o = run_heads(B.minf_bs_attn, q, k, v, [0], dev)
+    clean_idx = np.array([[0, -1, -1], [0, 1, -1], [1, 2, -1], [0, 3, -1]])
+    want = O.bs_attention(to_f64(q[0]), to_f64(k[0]), to_f64(v[0]), clean_idx, np.array([1, 2, 2, 2]))
+    assert_close_rows(o[0], want, "bs bad ids")
+
+
+VS_CASES = [
+    # (N, verticals, slashes)
+    (512, [3, 70, 71, 300, 511], [0, 5, 64, 200, 201, 450]),
+    (1024, list(range(0, 1024, 37)), [0, 1, 2, 3, 130, 131, 400, 1000]),
+    (1024, [0], [0]),                                   # only-slash / only-vertical limits
+    (768, list(range(768)), [0]),                       # every vertical: dense
+    (768, [5], list(range(768))),                       # every slash: dense
+    (640, [600, 601], [500]),                           # early blocks have no permitted key
+]
+
+
+@pytest.mark.parametrize("N,Vl,Sl", VS_CASES)
+def test_vs_matches_oracle(B, N, Vl, Sl):
+    q, k, v = random_qkv(7, 2, 1, N)
+    dev = B.vs_index_from_host([Vl, Vl], [Sl, Sl], N)
+    o = run_heads(B.minf_vs_attn, q, k, v, [0, 1], dev)
+    for h in (0, 1):
+        want = O.vs_attention(to_f64(q[h]), to_f64(k[0]), to_f64(v[0]), Vl, Sl, Bm=64)
+        assert_close_rows(o[h], want, f"vs N={N} head {h}")
+
+
+def test_vs_many_columns_more_than_one_round(B, rng):
+    # more kept verticals than one LDS round holds (1024): the column phase runs twice
+    N = 2048
+    q, k, v = random_qkv(8, 1, 1, N)
+    Vl = sorted(rng.choice(N, 1500, replace=False).tolist())
+    Sl = [0, 777]
+    dev = B.vs_index_from_host([Vl], [Sl], N)
+    o = run_heads(B.minf_vs_attn, q, k, v, [0], dev)
+    want = O.vs_attention(to_f64(q[0]), to_f64(k[0]), to_f64(v[0]), Vl, Sl, Bm=64)
+    assert_close_rows(o[0], want, "vs 1500 columns")
+
+
+def test_bad_arguments_are_rejected_before_launch(B):
+    q, k, v = random_qkv(9, 2, 1, 128)
+    o = torch.zeros_like(q)
+    with pytest.raises(B.MinfError) as e:
+        B.minf_ashape_attn(q, k, v, o, [5], 64, 64)           # head id out of range
+    assert e.value.status == 2
+    with pytest.raises(B.MinfError) as e:
+        B.minf_ashape_attn(q, k, v, o, [0], 64, 0)            # n_local < 1
+    assert e.value.status == 3
+    with pytest.raises(B.MinfError) as e:
+        B.minf_dense_attn(q[:, :100], k[:, :100], v[:, :100], o[:, :100], [0])   # N % 64 != 0
+    assert e.value.status == 2
+    assert (o == 0).all()
