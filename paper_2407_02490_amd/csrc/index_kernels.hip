@@ -1,11 +1,641 @@
-// placeholder, replaced below
-#include "minf_internal.h"
+// Online sparse-index construction for gfx950 (MI355X).
+//
+// Vertical-Slash (Alg. 2, first steps; App. C.4.2):
+//   A_hat = softmax(Q[-64:] K^T / sqrt(d) + causal), column sums, diagonal sums,
+//   exact top-k of both, ascending sort, merge of the 64-wide slash tiles into
+//   offset runs + a run bitmap.
+//   K is streamed twice: pass 1 gives the row max / row sum of the 64 estimating
+//   queries per key chunk (combined afterwards in a fixed order), pass 2 forms
+//   the normalised probabilities and reduces them along columns and diagonals.
+//   A_hat itself (64 x N) is never stored.  All reductions run in a fixed
+//   order: the scores are bit-reproducible.
+// Block-Sparse (Alg. 3, first steps):
+//   mean pooling of Q and K over 64-token blocks (fp32), block logits with the
+//   fp32 MFMA (the selection needs fp32-class logits), per-row exact top-k.
+// Top-k is an exact radix select on the order-preserving integer image of the
+// fp32 score (4 passes of 8 bits), ties to the lower index, followed by an
+// ordered compaction, so the kept indices come out ascending without a sort.
+#include "mfma_tile.h"
+
 namespace minf {
-size_t vs_index_ws_bytes(int N, int n_heads) { return 256; }
-size_t bs_index_ws_bytes(int N, int n_heads) { return 256; }
+
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+
+constexpr int VS_CHUNK = 1024;      // keys / offsets owned by one workgroup of the score kernels
+constexpr int P_PITCH = 68;         // floats per LDS row of the probability tile
+
+struct KvMap {                      // pooling work list of the Block-Sparse build
+  int32_t n_kv;                     // distinct KV heads used by the call
+  int32_t kv[MINF_MAX_HEADS];       // their ids
+  int32_t slot_kv[MINF_MAX_HEADS];  // head slot -> position in kv[]
+};
+
+// ---------------------------------------------------------------------------
+// helpers: order-preserving key, block-wide radix select, ordered compaction
+// ---------------------------------------------------------------------------
+__device__ inline unsigned order_key(float f) {
+  unsigned u = __float_as_uint(f);
+  return u ^ ((u >> 31) ? 0xffffffffu : 0x80000000u);
+}
+
+__device__ inline unsigned long long lanes_below(int lane) { return (1ull << lane) - 1ull; }
+
+// Finds the k-th largest of data[0..n) (1 <= k <= n).  On return *thr is its
+// key and *take_eq the number of elements equal to it that belong to the top-k
+// (to be taken in index order).  hist: 256 ints of LDS, sh: 4 ints of LDS.
+template <int NT>
+__device__ inline void radix_select(const float *data, int n, int k, unsigned *thr, int *take_eq,
+                                    int *hist, int *sh) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  unsigned prefix = 0, mask = 0;
+  int krem = k;
+  for (int pass = 3; pass >= 0; --pass) {
+    const int shift = 8 * pass;
+    for (int i = tid; i < 256; i += NT) hist[i] = 0;
+    __syncthreads();
+    const int n_round = (n + NT - 1) / NT * NT;
+    for (int i = tid; i < n_round; i += NT) {
+      bool part = false;
+      int d = 0;
+      if (i < n) {
+        const unsigned u = order_key(data[i]);
+        part = (u & mask) == prefix;
+        d = (u >> shift) & 255;
+      }
+      // Scores of one row often share their leading byte: add that byte's count
+      // once per wave instead of 64 colliding LDS atomics.
+      const unsigned long long bal = __builtin_amdgcn_ballot_w64(part);
+      if (bal) {
+        const int lead = __builtin_ctzll(bal);
+        const int dl = __shfl(d, lead);
+        const unsigned long long same = __builtin_amdgcn_ballot_w64(part && d == dl);
+        if (lane == lead) atomicAdd(&hist[dl], __builtin_popcountll(same));
+        if (part && d != dl) atomicAdd(&hist[d], 1);
+      }
+    }
+    __syncthreads();
+    // suffix sums over the 256 bins by the first 256 threads (4 waves)
+    int suf = 0, own = 0;
+    if (tid < 256) {
+      own = hist[tid];
+      suf = own;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_down(suf, off);
+        if (lane + off < 64) suf += o;
+      }
+      if (lane == 0) sh[tid >> 6] = suf;      // wave totals
+    }
+    __syncthreads();
+    if (tid < 256) {
+      for (int w = (tid >> 6) + 1; w < 4; ++w) suf += sh[w];
+      // suf = number of candidates with digit >= tid
+      if (suf >= krem && suf - own < krem) {
+        sh[4] = tid;
+        sh[5] = krem - (suf - own);
+      }
+    }
+    __syncthreads();
+    prefix |= (unsigned)sh[4] << shift;
+    mask |= 255u << shift;
+    krem = sh[5];
+    __syncthreads();
+  }
+  *thr = prefix;
+  *take_eq = krem;
+}
+
+// Writes, ascending, the indices i with key(data[i]) > thr plus the first
+// take_eq indices with key == thr.  Each wave owns a contiguous range; counts
+// are exchanged through sh (2 * NT/64 ints of LDS).
+template <int NT>
+__device__ inline void ordered_select(const float *data, int n, unsigned thr, int take_eq, int32_t *out,
+                                      int *sh) {
+  constexpr int NW = NT / 64;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int per = ((n + NW - 1) / NW + 63) / 64 * 64;
+  const int lo = min(wave * per, n), hi = min(lo + per, n);
+  int gt = 0, eq = 0;
+  for (int i0 = lo; i0 < hi; i0 += 64) {
+    const int i = i0 + lane;
+    unsigned u = 0;
+    const bool in = i < hi;
+    if (in) u = order_key(data[i]);
+    gt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(in && u > thr));
+    eq += __builtin_popcountll(__builtin_amdgcn_ballot_w64(in && u == thr));
+  }
+  if (lane == 0) { sh[wave] = gt; sh[NW + wave] = eq; }
+  __syncthreads();
+  int pos = 0, eq_before = 0;
+  for (int w = 0; w < wave; ++w) {
+    const int e = sh[NW + w];
+    pos += sh[w] + max(0, min(e, take_eq - eq_before));
+    eq_before += e;
+  }
+  for (int i0 = lo; i0 < hi; i0 += 64) {
+    const int i = i0 + lane;
+    unsigned u = 0;
+    const bool in = i < hi;
+    if (in) u = order_key(data[i]);
+    const bool g = in && u > thr, e = in && u == thr;
+    const unsigned long long eb = __builtin_amdgcn_ballot_w64(e);
+    const int rank = eq_before + __builtin_popcountll(eb & lanes_below(lane));
+    const bool sel = g || (e && rank < take_eq);
+    const unsigned long long sb = __builtin_amdgcn_ballot_w64(sel);
+    if (sel) out[pos + __builtin_popcountll(sb & lanes_below(lane))] = i;
+    pos += __builtin_popcountll(sb);
+    eq_before += __builtin_popcountll(eb);
+  }
+  __syncthreads();
+}
+
+// ---------------------------------------------------------------------------
+// K tile staging for the estimate (K only, one wave)
+// ---------------------------------------------------------------------------
+struct KRegs { uint4 k[16]; };
+
+__device__ inline void ktile_issue(KRegs &r, const bf16_t *kh, int64_t k_st, int kbase, int lane) {
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int c = lane + 64 * i, row = c >> 4, col = c & 15;
+    r.k[i] = *reinterpret_cast<const uint4 *>(kh + (int64_t)(kbase + row) * k_st + col * 8);
+  }
+}
+__device__ inline void ktile_store(const KRegs &r, bf16_t *ldsK, int lane) {
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int c = lane + 64 * i, row = c >> 4, col = c & 15;
+    *reinterpret_cast<uint4 *>(ldsK + row * K_PITCH + col * 8) = r.k[i];
+  }
+}
+
+// S^T = K Q^T for one 64-key tile; register r of s[mb][nb] holds key index
+// 32mb + 16(r/8) + 8h + (r%8) and estimating row 32nb + n (n = lane%32, h = lane/32).
+__device__ inline void logits_tile(f32x16 (&s)[2][2], const bf16x8 (&q)[2][8], const bf16_t *ldsK, int lane) {
+  const int n = lane & 31, h = lane >> 5, prow = perm_row(n);
+#pragma unroll
+  for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[mb][nb][r] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) {
+      bf16x8 a = *reinterpret_cast<const bf16x8 *>(ldsK + (32 * mb + prow) * K_PITCH + 16 * ks + 8 * h);
+      s[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[0][ks], s[mb][0], 0, 0, 0);
+      s[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[1][ks], s[mb][1], 0, 0, 0);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Vertical-Slash score kernels.  Estimating row r (0..63) is query N-64+r; rows
+// r < 64 - last_q do not take part.  Workgroup (head slot, chunk c) owns the
+// offsets [cC, cC+C) and the keys [N-cC-C, N-cC): tile m of the chunk holds the
+// keys [N-cC-64(m+1), N-cC-64m); offsets of the chunk meet only tiles 0..C/64.
+// ---------------------------------------------------------------------------
+template <int PASS>
+__global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int last_q, int n_chunks,
+                                                      float *ml_part, const float *ml_fin,
+                                                      float *colsum, float *diagsum) {
+  extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
+  bf16_t *ldsK = lds;
+  float *P = reinterpret_cast<float *>(lds + K_TILE);          // [64][P_PITCH]
+  float *dacc = P + 64 * P_PITCH;                               // [VS_CHUNK]
+
+  const int slot = blockIdx.y, chunk = blockIdx.x;
+  const int head = hl.h[slot], kvh = head / x.group;
+  const bf16_t *qh = x.q + head * x.q_sh, *kh = x.k + kvh * x.k_sh;
+  const int lane = threadIdx.x, n = lane & 31, h = lane >> 5;
+  const int N = x.N, C = VS_CHUNK;
+  const int r_min = 64 - last_q;
+
+  bf16x8 q[2][8];
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) {
+    const bf16_t *row = qh + (int64_t)(N - 64 + 32 * nb + n) * x.q_st + 8 * h;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) q[nb][ks] = *reinterpret_cast<const bf16x8 *>(row + 16 * ks);
+  }
+
+  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+  float m_fin[2] = {0.f, 0.f}, inv_l[2] = {0.f, 0.f};
+  if (PASS == 2) {
+    for (int nb = 0; nb < 2; ++nb) {
+      m_fin[nb] = ml_fin[(slot * 64 + 32 * nb + n) * 2 + 0];
+      inv_l[nb] = ml_fin[(slot * 64 + 32 * nb + n) * 2 + 1];
+    }
+    for (int i = lane; i < C; i += 64) dacc[i] = 0.f;
+  }
+
+  const int key_hi = N - chunk * C;                 // exclusive end of the owned keys
+  const int n_tiles = PASS == 1 ? C / 64 : C / 64 + 1;
+  KRegs regs;
+  int m = 0;
+  auto tile_key = [&](int mm) { return key_hi - 64 * (mm + 1); };
+  if (tile_key(0) >= 0) ktile_issue(regs, kh, x.k_st, tile_key(0), lane);
+  for (; m < n_tiles; ++m) {
+    const int kt = tile_key(m);
+    if (kt < 0) break;                               // tiles are 64-aligned: wholly inside or outside
+    ktile_store(regs, ldsK, lane);
+    __syncthreads();
+    if (m + 1 < n_tiles && tile_key(m + 1) >= 0) ktile_issue(regs, kh, x.k_st, tile_key(m + 1), lane);
+    f32x16 s[2][2];
+    logits_tile(s, q, ldsK, lane);
+
+    if (PASS == 1) {
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        const int r = 32 * nb + n, p = N - 64 + r;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            const int key = kt + 32 * mb + 16 * (e >> 3) + 8 * h + (e & 7);
+            const bool ok = key <= p && r >= r_min;
+            const float v = ok ? s[mb][nb][e] * x.c_log2 : -INFINITY;
+            s[mb][nb][e] = v;
+            mx = fmaxf(mx, v);
+          }
+        const float m_new = fmaxf(m_run[nb], mx);
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;
+        float sum = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) sum += fast_exp2(s[mb][nb][e] - m_use);
+        l_run[nb] = l_run[nb] * fast_exp2(m_run[nb] - m_use) + sum;
+        m_run[nb] = m_new;
+      }
+    } else {
+      // probabilities -> LDS tile P[row][key index]
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) {
+        const int r = 32 * nb + n, p = N - 64 + r;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+          for (int t = 0; t < 2; ++t) {
+            float pv[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+              const int key = kt + 32 * mb + 16 * t + 8 * h + i;
+              const bool ok = key <= p && r >= r_min;
+              pv[i] = ok ? fast_exp2(fmaf(s[mb][nb][8 * t + i], x.c_log2, -m_fin[nb])) * inv_l[nb] : 0.f;
+            }
+            float *dst = P + r * P_PITCH + 32 * mb + 16 * t + 8 * h;
+            *reinterpret_cast<f32x4v *>(dst) = (f32x4v){pv[0], pv[1], pv[2], pv[3]};
+            *reinterpret_cast<f32x4v *>(dst + 4) = (f32x4v){pv[4], pv[5], pv[6], pv[7]};
+          }
+      }
+      __syncthreads();
+      // column sums of the owned keys (tiles 0 .. C/64-1): lane = key index
+      if (m < C / 64) {
+        float cs = 0.f;
+#pragma unroll 8
+        for (int r = 0; r < 64; ++r) cs += P[r * P_PITCH + lane];
+        colsum[(int64_t)slot * N + kt + lane] = cs;
+      }
+      // diagonal sums: element (r, key index c) lies on local offset 64m + r - c.
+      // lane handles delta = r - c in {lane - 63, lane + 1}.
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const int delta = half == 0 ? lane - 63 : lane + 1;
+        float ds = 0.f;
+#pragma unroll 8
+        for (int r = 0; r < 64; ++r) {
+          const int c = r - delta;
+          if (c >= 0 && c < 64) ds += P[r * P_PITCH + c];
+        }
+        const int local = 64 * m + delta;
+        if (local >= 0 && local < C) dacc[local] += ds;
+      }
+    }
+    __syncthreads();
+  }
+
+  if (PASS == 1) {
+    // merge the two lanes that share an estimating row, store the chunk's (max, sum)
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+      const float mo = __shfl_xor(m_run[nb], 32), lo = __shfl_xor(l_run[nb], 32);
+      const float M = fmaxf(m_run[nb], mo);
+      const float Mu = M == -INFINITY ? 0.f : M;
+      // same operand order in both lanes of the pair: lane-half 0's share first
+      const float a = h == 0 ? l_run[nb] * fast_exp2(m_run[nb] - Mu) : lo * fast_exp2(mo - Mu);
+      const float b = h == 0 ? lo * fast_exp2(mo - Mu) : l_run[nb] * fast_exp2(m_run[nb] - Mu);
+      if (h == 0) {
+        float *dst = ml_part + (((int64_t)slot * n_chunks + chunk) * 64 + 32 * nb + n) * 2;
+        dst[0] = M;
+        dst[1] = a + b;
+      }
+    }
+  } else {
+    for (int i = lane; i < C; i += 64) {
+      const int o = chunk * C + i;
+      if (o < N) diagsum[(int64_t)slot * N + o] = dacc[i];
+    }
+  }
+}
+
+// Combine the per-chunk (max, sum) pairs of every estimating row, in chunk
+// order, into (row max, 1 / row sum).
+__global__ __launch_bounds__(64) void vs_combine_kernel(int n_chunks, const float *ml_part, float *ml_fin) {
+  const int slot = blockIdx.x, r = threadIdx.x;
+  const float *src = ml_part + (int64_t)slot * n_chunks * 128;
+  float M = -INFINITY;
+  for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, src[(c * 64 + r) * 2]);
+  float L = 0.f;
+  if (M != -INFINITY)
+    for (int c = 0; c < n_chunks; ++c) L += src[(c * 64 + r) * 2 + 1] * fast_exp2(src[(c * 64 + r) * 2] - M);
+  ml_fin[(slot * 64 + r) * 2 + 0] = M == -INFINITY ? 0.f : M;
+  ml_fin[(slot * 64 + r) * 2 + 1] = L > 0.f ? 1.0f / L : 0.f;
+}
+
+// Top-k + "sparseformat".  blockIdx.y = 0: verticals from the column sums;
+// blockIdx.y = 1: slashes from the diagonal sums, their runs and the run bitmap.
+__global__ __launch_bounds__(1024) void vs_select_kernel(int N, int nv, int ns, const float *colsum,
+                                                         const float *diagsum, int32_t *v_idx,
+                                                         int32_t *s_idx, int32_t *cover,
+                                                         uint32_t *cover_bits, int32_t *counts,
+                                                         int cover_words) {
+  __shared__ int hist[256];
+  __shared__ int sh[40];
+  const int slot = blockIdx.x, which = blockIdx.y, tid = threadIdx.x;
+  const float *data = (which == 0 ? colsum : diagsum) + (int64_t)slot * N;
+  const int kcap = which == 0 ? nv : ns;
+  const int k = min(kcap, N);
+  int32_t *out = which == 0 ? v_idx + (int64_t)slot * nv : s_idx + (int64_t)slot * ns;
+  unsigned thr;
+  int take_eq;
+  radix_select<1024>(data, N, k, &thr, &take_eq, hist, sh);
+  ordered_select<1024>(data, N, thr, take_eq, out, sh + 8);
+  for (int i = k + tid; i < kcap; i += 1024) out[i] = 0;
+  if (which == 0) {
+    if (tid == 0) counts[slot * 4 + 0] = k;
+    return;
+  }
+  // ---- slash runs: a gap of more than 64 between neighbouring kept offsets ends a run
+  uint32_t *bits = cover_bits + (int64_t)slot * cover_words;
+  for (int i = tid; i < cover_words; i += 1024) bits[i] = 0u;
+  __threadfence_block();
+  __syncthreads();
+  int2 *runs = reinterpret_cast<int2 *>(cover) + (int64_t)slot * ns;
+  int run_base = 0;
+  const int lane = tid & 63, wave = tid >> 6;
+  for (int i0 = 0; i0 < k; i0 += 1024) {
+    const int i = i0 + tid;
+    int o = 0;
+    bool start = false, last = false;
+    if (i < k) {
+      o = out[i];
+      start = i == 0 || o - out[i - 1] > 64;
+      last = i == k - 1 || out[i + 1] - o > 64;
+    }
+    const unsigned long long sb = __builtin_amdgcn_ballot_w64(start);
+    if (lane == 0) sh[8 + wave] = __builtin_popcountll(sb);
+    __syncthreads();
+    int before = run_base, total = 0;
+    for (int w = 0; w < 16; ++w) {
+      const int c = sh[8 + w];
+      if (w < wave) before += c;
+      total += c;
+    }
+    // run id of element i = (number of starts at or before i) - 1
+    const int rid = before + __builtin_popcountll(sb & lanes_below(lane)) + (start ? 1 : 0) - 1;
+    if (start) runs[rid].x = o - 63;
+    if (last) runs[rid].y = o + 1;
+    if (i < k) {
+      // offsets o-63 .. o  ->  bits o+1 .. o+64
+      const int b0 = o + 1, b1 = o + 64;
+      const int w0 = b0 >> 5, w1 = b1 >> 5;
+      for (int w = w0; w <= w1; ++w) {
+        const int lo = max(b0, w * 32) - w * 32, hi = min(b1, w * 32 + 31) - w * 32;
+        const unsigned msk = (hi == 31 ? 0xffffffffu : ((1u << (hi + 1)) - 1u)) & ~((1u << lo) - 1u);
+        atomicOr(&bits[w], msk);
+      }
+    }
+    run_base += total;
+    __syncthreads();
+  }
+  if (tid == 0) {
+    counts[slot * 4 + 1] = k;
+    counts[slot * 4 + 2] = run_base;
+    counts[slot * 4 + 3] = 0;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// Block-Sparse: pooling, block logits, per-row top-k
+// ---------------------------------------------------------------------------
+// grid (NB, n_heads + n_kv): y < n_heads pools Q of head slot y, else K of kv[y - n_heads]
+__global__ __launch_bounds__(256) void bs_pool_kernel(QKV x, HeadList hl, KvMap km, float *qpool, float *kpool) {
+  __shared__ float red[16][132];
+  const int b = blockIdx.x, y = blockIdx.y, NB = x.N / 64;
+  const bf16_t *src;
+  int64_t st;
+  float *dst;
+  if (y < hl.n) {
+    src = x.q + hl.h[y] * x.q_sh; st = x.q_st; dst = qpool + ((int64_t)y * NB + b) * 128;
+  } else {
+    src = x.k + km.kv[y - hl.n] * x.k_sh; st = x.k_st; dst = kpool + ((int64_t)(y - hl.n) * NB + b) * 128;
+  }
+  const int tid = threadIdx.x, r = tid >> 4, c = tid & 15;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const uint4 w = *reinterpret_cast<const uint4 *>(src + (int64_t)(b * 64 + r + 16 * i) * st + c * 8);
+    const unsigned ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      acc[2 * j] += __uint_as_float(ww[j] << 16);
+      acc[2 * j + 1] += __uint_as_float(ww[j] & 0xffff0000u);
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < 8; ++j) red[r][c * 8 + j] = acc[j];
+  __syncthreads();
+  if (tid < 128) {
+    float s = 0.f;
+#pragma unroll
+    for (int rr = 0; rr < 16; ++rr) s += red[rr][tid];
+    dst[tid] = s * (1.0f / 64.0f);
+  }
+}
+
+// Block logits of the lower triangle, one wave per 64 x 64 tile, fp32 MFMA
+// (v_mfma_f32_32x32x2_f32).  grid (tiles of the lower triangle, heads of the batch).
+__global__ __launch_bounds__(64) void bs_logits_kernel(int NB, int slot0, KvMap km, const float *qpool,
+                                                       const float *kpool, float *scores, float scale) {
+  const int t = blockIdx.x, hb = blockIdx.y, slot = slot0 + hb;
+  // t -> (ti, tj), tj <= ti
+  int ti = (int)((sqrtf(8.0f * (float)t + 1.0f) - 1.0f) * 0.5f);
+  while ((ti + 1) * (ti + 2) / 2 <= t) ++ti;
+  while (ti * (ti + 1) / 2 > t) --ti;
+  const int tj = t - ti * (ti + 1) / 2;
+  const int lane = threadIdx.x, n = lane & 31, h = lane >> 5;
+  const float *qp = qpool + (int64_t)slot * NB * 128;
+  const float *kp = kpool + (int64_t)km.slot_kv[slot] * NB * 128;
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+  const float *arow[2], *brow[2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+    arow[a] = qp + (int64_t)min(ti * 64 + 32 * a + n, NB - 1) * 128 + 8 * h;
+    brow[a] = kp + (int64_t)min(tj * 64 + 32 * a + n, NB - 1) * 128 + 8 * h;
+  }
+  // contraction index of step (ch, i): d = 16ch + 8h + i, the same for both operands
+#pragma unroll 2
+  for (int ch = 0; ch < 8; ++ch) {
+    float av[2][8], bv[2][8];
+#pragma unroll
+    for (int a = 0; a < 2; ++a) {
+      const f32x4v a0 = *reinterpret_cast<const f32x4v *>(arow[a] + 16 * ch);
+      const f32x4v a1 = *reinterpret_cast<const f32x4v *>(arow[a] + 16 * ch + 4);
+      const f32x4v b0 = *reinterpret_cast<const f32x4v *>(brow[a] + 16 * ch);
+      const f32x4v b1 = *reinterpret_cast<const f32x4v *>(brow[a] + 16 * ch + 4);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { av[a][i] = a0[i]; av[a][4 + i] = a1[i]; bv[a][i] = b0[i]; bv[a][4 + i] = b1[i]; }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[a][i], bv[b][i], acc[a][b], 0, 0, 0);
+  }
+  float *out = scores + (int64_t)hb * NB * NB;
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = ti * 64 + 32 * a + (r >> 2) * 8 + 4 * h + (r & 3);
+        const int col = tj * 64 + 32 * b + n;
+        if (row < NB && col < NB) out[(int64_t)row * NB + col] = acc[a][b][r] * scale;
+      }
+}
+
+// grid (NB, heads of the batch): row b keeps its min(topk, b+1) largest logits among c <= b
+__global__ __launch_bounds__(256) void bs_select_kernel(int NB, int slot0, int topk, const float *scores,
+                                                        int32_t *blk_idx, int32_t *blk_cnt) {
+  __shared__ int hist[256];
+  __shared__ int sh[24];
+  const int b = blockIdx.x, hb = blockIdx.y, slot = slot0 + hb, tid = threadIdx.x;
+  const float *row = scores + ((int64_t)hb * NB + b) * NB;
+  int32_t *out = blk_idx + ((int64_t)slot * NB + b) * topk;
+  const int n = b + 1, k = min(topk, n);
+  if (n <= topk) {
+    for (int i = tid; i < topk; i += 256) out[i] = i < n ? i : -1;
+  } else {
+    unsigned thr;
+    int take_eq;
+    radix_select<256>(row, n, k, &thr, &take_eq, hist, sh);
+    ordered_select<256>(row, n, thr, take_eq, out, sh + 8);
+  }
+  if (tid == 0) blk_cnt[(int64_t)slot * NB + b] = k;
+}
+
+// ---------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------
+static inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
+
+static int vs_chunks(int N) { return (N + VS_CHUNK - 1) / VS_CHUNK; }
+
+size_t vs_index_ws_bytes(int N, int n_heads) {
+  size_t b = 0;
+  b += 2 * align256((size_t)n_heads * N * sizeof(float));                     // colsum, diagsum
+  b += align256((size_t)n_heads * vs_chunks(N) * 128 * sizeof(float));        // per-chunk (max, sum)
+  b += align256((size_t)n_heads * 128 * sizeof(float));                       // final (max, 1/sum)
+  return b;
+}
+
 hipError_t launch_build_vs(const QKV &x, const HeadList &hl, int last_q, int nv, int ns,
                            int32_t *v_idx, int32_t *s_idx, int32_t *cover, uint32_t *cover_bits,
-                           int32_t *counts, int cover_words, void *ws, hipStream_t st) { return hipErrorNotSupported; }
-hipError_t launch_build_bs(const QKV &x, const HeadList &hl, int topk, int32_t *blk_idx,
-                           int32_t *blk_cnt, void *ws, hipStream_t st) { return hipErrorNotSupported; }
+                           int32_t *counts, int cover_words, void *ws, hipStream_t st) {
+  const int N = x.N, nc = vs_chunks(N);
+  char *p = static_cast<char *>(ws);
+  float *colsum = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * N * sizeof(float));
+  float *diagsum = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * N * sizeof(float));
+  float *ml_part = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * nc * 128 * sizeof(float));
+  float *ml_fin = reinterpret_cast<float *>(p);
+  const size_t lds = K_TILE * sizeof(bf16_t) + (64 * P_PITCH + VS_CHUNK) * sizeof(float);
+  hipError_t e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(vs_score_kernel<1>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(vs_score_kernel<2>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (e != hipSuccess) return e;
+  const dim3 grid(nc, hl.n);
+  hipLaunchKernelGGL(vs_score_kernel<1>, grid, dim3(64), lds, st, x, hl, last_q, nc, ml_part,
+                     (const float *)nullptr, (float *)nullptr, (float *)nullptr);
+  hipLaunchKernelGGL(vs_combine_kernel, dim3(hl.n), dim3(64), 0, st, nc, (const float *)ml_part, ml_fin);
+  hipLaunchKernelGGL(vs_score_kernel<2>, grid, dim3(64), lds, st, x, hl, last_q, nc, (float *)nullptr,
+                     (const float *)ml_fin, colsum, diagsum);
+  hipLaunchKernelGGL(vs_select_kernel, dim3(hl.n, 2), dim3(1024), 0, st, N, nv, ns, (const float *)colsum,
+                     (const float *)diagsum, v_idx, s_idx, cover, cover_bits, counts, cover_words);
+  return hipGetLastError();
 }
+
+// Block logits are staged in the workspace for at most this many bytes at a
+// time; heads are processed in batches that fit.
+static const size_t BS_SCORE_CAP = (size_t)2 << 30;
+
+static int bs_head_batch(int NB, int n_heads) {
+  const size_t per = (size_t)NB * NB * sizeof(float);
+  size_t hb = BS_SCORE_CAP / per;
+  if (hb < 1) hb = 1;
+  return (int)(hb < (size_t)n_heads ? hb : (size_t)n_heads);
+}
+
+size_t bs_index_ws_bytes(int N, int n_heads) {
+  const int NB = N / 64;
+  size_t b = 0;
+  b += 2 * align256((size_t)n_heads * NB * 128 * sizeof(float));              // pooled Q, pooled K
+  b += align256((size_t)bs_head_batch(NB, n_heads) * NB * NB * sizeof(float)); // block logits
+  return b;
+}
+
+hipError_t launch_build_bs(const QKV &x, const HeadList &hl, int topk, int32_t *blk_idx,
+                           int32_t *blk_cnt, void *ws, hipStream_t st) {
+  const int NB = x.N / 64;
+  KvMap km;
+  km.n_kv = 0;
+  for (int i = 0; i < hl.n; ++i) {
+    const int kv = hl.h[i] / x.group;
+    int j = 0;
+    while (j < km.n_kv && km.kv[j] != kv) ++j;
+    if (j == km.n_kv) km.kv[km.n_kv++] = kv;
+    km.slot_kv[i] = j;
+  }
+  for (int i = hl.n; i < MINF_MAX_HEADS; ++i) km.slot_kv[i] = 0;
+  for (int i = km.n_kv; i < MINF_MAX_HEADS; ++i) km.kv[i] = 0;
+  char *p = static_cast<char *>(ws);
+  float *qpool = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * NB * 128 * sizeof(float));
+  float *kpool = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * NB * 128 * sizeof(float));
+  float *scores = reinterpret_cast<float *>(p);
+  hipLaunchKernelGGL(bs_pool_kernel, dim3(NB, hl.n + km.n_kv), dim3(256), 0, st, x, hl, km, qpool, kpool);
+  const int hbmax = bs_head_batch(NB, hl.n);
+  const int TB = (NB + 63) / 64, n_tiles = TB * (TB + 1) / 2;
+  for (int s0 = 0; s0 < hl.n; s0 += hbmax) {
+    const int hb = hl.n - s0 < hbmax ? hl.n - s0 : hbmax;
+    hipLaunchKernelGGL(bs_logits_kernel, dim3(n_tiles, hb), dim3(64), 0, st, NB, s0, km,
+                       (const float *)qpool, (const float *)kpool, scores, x.scale);
+    hipLaunchKernelGGL(bs_select_kernel, dim3(NB, hb), dim3(256), 0, st, NB, s0, topk,
+                       (const float *)scores, blk_idx, blk_cnt);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace minf

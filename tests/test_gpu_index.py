@@ -1,0 +1,162 @@
+"""Parity of the HIP index builders with the CPU oracle, through the C ABI.
+
+Index sets must equal the oracle's exact top-k except for swaps among scores
+that tie within 1e-3 of the k-th score (tests/helpers.check_topk); the merged
+slash runs and the run bitmap are integer work and must be exact functions of
+the kept offsets.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import minference_oracle as O
+from paper_2407_02490_amd import workloads as W
+from tests.helpers import assert_close_rows, check_topk, random_qkv, to_f64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2407_02490_amd import binding
+    binding.lib()
+    return binding
+
+
+def build_vs(B, q, k, heads, last_q, nv, ns):
+    N = q.shape[-2]
+    idx = B.alloc_vs_index(len(heads), nv, ns, N)
+    ws = torch.empty(B.minf_vs_index_workspace_bytes(q, k, len(heads), last_q), dtype=torch.uint8, device="cuda")
+    B.minf_build_vs_index(q, k, heads, last_q, nv, ns, idx, ws)
+    torch.cuda.synchronize()
+    return idx
+
+
+def check_vs_index(idx, r, N, Qh, Kh, last_q, nv, ns):
+    Vo, So, col, diag = O.vs_index(Qh, Kh, last_q, nv, ns)
+    n_v, n_s, n_c, _ = idx.counts[r].cpu().tolist()
+    assert n_v == min(nv, N) and n_s == min(ns, N)
+    Vg = idx.v_idx[r, :n_v].cpu().numpy()
+    Sg = idx.s_idx[r, :n_s].cpu().numpy()
+    swaps = check_topk(Vg, col, nv) + check_topk(Sg, diag, ns)
+    # runs and bitmap: exact functions of the kept offsets (compared with the
+    # oracle's cover of the GPU's own offsets)
+    cover = O.slash_cover(Sg, N, 64)                       # index t + 64, t in [-64, N)
+    runs = idx.cover[r, :n_c].cpu().numpy()
+    c8 = cover.astype(np.int8)
+    edges = np.diff(np.concatenate([[0], c8, [0]]))
+    t0 = np.flatnonzero(edges == 1) - 64
+    t1 = np.flatnonzero(edges == -1) - 64
+    assert n_c == t0.size
+    assert np.array_equal(runs[:, 0], t0) and np.array_equal(runs[:, 1], t1)
+    bits = idx.cover_bits[r].cpu().numpy().view(np.uint32)
+    flat = np.unpackbits(bits.view(np.uint8), bitorder="little")
+    assert np.array_equal(flat[:N + 64].astype(bool), cover)
+    assert not flat[N + 64:].any()
+    return Vg, Sg, swaps
+
+
+@pytest.mark.parametrize("N,last_q,nv,ns", [(1024, 64, 30, 50), (4096, 64, 256, 512), (2112, 17, 100, 3000),
+                                             (64, 64, 5, 5), (1088, 1, 7, 9)])
+def test_vs_index_random_inputs(B, N, last_q, nv, ns):
+    q, k, v = random_qkv(11, 4, 2, N)
+    heads = [2, 0, 3]
+    idx = build_vs(B, q, k, heads, last_q, nv, ns)
+    for r, h in enumerate(heads):
+        check_vs_index(idx, r, N, to_f64(q[h]), to_f64(k[h // 2]), last_q, nv, ns)
+
+
+def test_vs_index_is_bit_reproducible(B):
+    q, k, v = random_qkv(12, 2, 1, 2048)
+    a = build_vs(B, q, k, [0, 1], 64, 100, 200)
+    b = build_vs(B, q, k, [0, 1], 64, 100, 200)
+    for name in ("v_idx", "s_idx", "cover_bits", "counts"):
+        assert torch.equal(getattr(a, name), getattr(b, name))
+
+
+def test_c0_vertical_slash_layer_end_to_end(B):
+    """Workload c0 in full: index build + attention on all rows of all heads."""
+    x = W.make_config("c0")
+    q, k, v = x.q.cuda(), x.k.cuda(), x.v.cuda()
+    N, heads = x.seq_len, [0, 1, 2, 3]
+    idx = build_vs(B, q, k, heads, 64, 256, 512)
+    o = torch.zeros_like(q)
+    B.minf_vs_attn(q, k, v, o, heads, idx)
+    torch.cuda.synchronize()
+    total_swaps = 0
+    for r, h in enumerate(heads):
+        Qh, Kh, Vh = x.head_f64(h)
+        Vg, Sg, swaps = check_vs_index(idx, r, N, Qh, Kh, 64, 256, 512)
+        total_swaps += swaps
+        # planted sinks are found as verticals
+        assert np.isin(x.sinks[h].numpy(), Vg).mean() >= 0.9
+        want = O.vs_attention(Qh, Kh, Vh, Vg, Sg, Bm=64)
+        assert_close_rows(o[h], want, f"c0 head {h}")
+    assert total_swaps == 0
+
+
+def build_bs(B, q, k, heads, topk):
+    N = q.shape[-2]
+    idx = B.alloc_bs_index(len(heads), N, topk)
+    ws = torch.empty(B.minf_bs_index_workspace_bytes(q, k, len(heads)), dtype=torch.uint8, device="cuda")
+    B.minf_build_bs_index(q, k, heads, topk, idx, ws)
+    torch.cuda.synchronize()
+    return idx
+
+
+def check_bs_index(idx, r, Qh, Kh, topk):
+    _, cnt_o, s = O.bs_index(Qh, Kh, 64, topk)
+    NB = s.shape[0]
+    got = idx.blk_idx[r].cpu().numpy()
+    cnt = idx.blk_cnt[r].cpu().numpy()
+    assert np.array_equal(cnt, cnt_o)
+    swaps = 0
+    for b in range(NB):
+        assert np.all(got[b, cnt[b]:] == -1)
+        swaps += check_topk(got[b, :cnt[b]], s[b, :b + 1], topk, relative=False)
+    return got, cnt, swaps
+
+
+@pytest.mark.parametrize("N,topk", [(1024, 4), (4096, 16), (1344, 100), (64, 3)])
+def test_bs_index_random_inputs(B, N, topk):
+    q, k, v = random_qkv(13, 4, 2, N)
+    heads = [1, 2, 0]
+    idx = build_bs(B, q, k, heads, topk)
+    for r, h in enumerate(heads):
+        check_bs_index(idx, r, to_f64(q[h]), to_f64(k[h // 2]), topk)
+
+
+def test_bs_clustered_layer_end_to_end(B):
+    """Workload c3's recipe at a reduced length: index build + attention."""
+    x = W.make_config("c3", N=8192, n_q_heads=4, n_kv_heads=2)
+    q, k, v = x.q.cuda(), x.k.cuda(), x.v.cuda()
+    heads = [0, 1, 2, 3]
+    idx = build_bs(B, q, k, heads, 20)
+    o = torch.zeros_like(q)
+    B.minf_bs_attn(q, k, v, o, heads, idx)
+    torch.cuda.synchronize()
+    for r, h in enumerate(heads):
+        Qh, Kh, Vh = x.head_f64(h)
+        got, cnt, swaps = check_bs_index(idx, r, Qh, Kh, 20)
+        want = O.bs_attention(Qh, Kh, Vh, got, cnt)
+        assert_close_rows(o[h], want, f"clustered bs head {h}")
+
+
+def test_index_argument_errors(B):
+    q, k, v = random_qkv(14, 2, 1, 256)
+    idx = B.alloc_vs_index(1, 10, 10, 256)
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.MinfError) as e:
+        B.minf_build_vs_index(q, k, [0], 64, 10, 10, idx, small)
+    assert e.value.status == 4
+    ws = torch.empty(B.minf_vs_index_workspace_bytes(q, k, 1, 64), dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.MinfError) as e:
+        B.minf_build_vs_index(q, k, [0], 65, 10, 10, idx, ws)       # last_q > 64
+    assert e.value.status == 3
+    with pytest.raises(B.MinfError) as e:
+        B.minf_build_vs_index(q, k, [0], 64, 10, 0, idx, ws)        # needs at least one slash
+    assert e.value.status == 3
+    bidx = B.alloc_bs_index(1, 256, 4)
+    with pytest.raises(B.MinfError) as e:
+        B.minf_build_bs_index(q, k, [0], 4, bidx, ws, block=32)
+    assert e.value.status == 5
