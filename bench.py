@@ -1,0 +1,331 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse-prefill attention hot path on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic layer: for the
+default workload (c4: the mixed-pattern 1M-token layer, 24 Vertical-Slash +
+6 Block-Sparse + 2 A-shape heads) that is both index builds and the three
+attention calls, timed end to end with the inputs resident in HBM.  The same
+run also reports the three single-pattern 128K layers (c1, c2, c3), our dense
+causal kernel at both lengths for the speedup column, and the CPU oracle timed
+on a bounded sample of the workload.
+
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2407_02490_amd import binding as B          # noqa: E402
+from paper_2407_02490_amd import costmodel as C        # noqa: E402
+from paper_2407_02490_amd import workloads as W        # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0
+FT = C.tile_flops()
+
+
+def log(*a):
+    print("[bench]", *a, file=sys.stderr, flush=True)
+
+
+def u8(nbytes):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda")
+
+
+class Timer:
+    """HIP event pairs on torch's current stream (the stream every call here is enqueued on)."""
+
+    def __init__(self):
+        self.pairs = []
+
+    def __enter__(self):
+        self.a = torch.cuda.Event(enable_timing=True)
+        self.b = torch.cuda.Event(enable_timing=True)
+        self.a.record()
+        return self
+
+    def __exit__(self, *exc):
+        self.b.record()
+        self.pairs.append((self.a, self.b))
+
+    def ms(self):
+        return [a.elapsed_time(b) for a, b in self.pairs]
+
+    def reset(self):
+        self.pairs = []
+
+
+class Layer:
+    """One workload: buffers, the step function, tile counts."""
+
+    def __init__(self, name):
+        self.name = name
+        c = W.CONFIGS[name]
+        self.cfg = c
+        t0 = time.time()
+        self.x = W.make_config(name, device="cuda")
+        torch.cuda.synchronize()
+        log(f"{name}: inputs generated in {time.time() - t0:.1f}s")
+        x = self.x
+        self.N, self.Hq = x.seq_len, x.n_q_heads
+        self.o = torch.empty_like(x.q)
+        allh = list(range(self.Hq))
+        if c["pattern"] == "mixed":
+            self.vs_heads, self.bs_heads, self.a_heads = W.head_assignment(
+                self.Hq, c["n_vs"], c["n_bs"], c["n_ashape"])
+        else:
+            self.vs_heads = allh if c["pattern"] == "vs" else []
+            self.bs_heads = allh if c["pattern"] == "bs" else []
+            self.a_heads = allh if c["pattern"] == "ashape" else []
+        if self.vs_heads:
+            self.vs_idx = B.alloc_vs_index(len(self.vs_heads), c["nv"], c["ns"], self.N)
+            self.vs_ws = u8(B.minf_vs_index_workspace_bytes(x.q, x.k, len(self.vs_heads), c["last_q"]))
+        if self.bs_heads:
+            self.bs_idx = B.alloc_bs_index(len(self.bs_heads), self.N, c["topk"])
+            self.bs_ws = u8(B.minf_bs_index_workspace_bytes(x.q, x.k, len(self.bs_heads)))
+        self.t = {k: Timer() for k in ("vs_index", "bs_index", "ashape_attn", "vs_attn", "bs_attn")}
+
+    def step(self):
+        x, c, t = self.x, self.cfg, self.t
+        if self.vs_heads:
+            with t["vs_index"]:
+                B.minf_build_vs_index(x.q, x.k, self.vs_heads, c["last_q"], c["nv"], c["ns"],
+                                      self.vs_idx, self.vs_ws)
+        if self.bs_heads:
+            with t["bs_index"]:
+                B.minf_build_bs_index(x.q, x.k, self.bs_heads, c["topk"], self.bs_idx, self.bs_ws)
+        if self.a_heads:
+            with t["ashape_attn"]:
+                B.minf_ashape_attn(x.q, x.k, x.v, self.o, self.a_heads, c["n_init"], c["n_local"])
+        if self.vs_heads:
+            with t["vs_attn"]:
+                B.minf_vs_attn(x.q, x.k, x.v, self.o, self.vs_heads, self.vs_idx)
+        if self.bs_heads:
+            with t["bs_attn"]:
+                B.minf_bs_attn(x.q, x.k, x.v, self.o, self.bs_heads, self.bs_idx)
+
+    def run(self, steps, warmup):
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        for t in self.t.values():
+            t.reset()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            self.step()
+        torch.cuda.synchronize()
+        wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+        return wall_ms
+
+    def tiles(self):
+        """Tile counts per attention call (whole call, all its heads)."""
+        out = {}
+        if self.a_heads:
+            out["ashape_attn"] = int(C.tiles_ashape(self.N, self.cfg["n_init"], self.cfg["n_local"]).sum()) * len(self.a_heads)
+        if self.vs_heads:
+            out["vs_attn"] = int(C.vs_index_tiles(self.vs_idx, self.N).sum())
+        if self.bs_heads:
+            out["bs_attn"] = int(C.bs_index_tiles(self.bs_idx).sum())
+        return out
+
+    def report(self, wall_ms):
+        tiles = self.tiles()
+        r = {"workload": self.name, "seq_len": self.N, "ms_per_layer": round(wall_ms, 4), "calls": {}}
+        tot_tiles = 0
+        for k, t in self.t.items():
+            ms = t.ms()
+            if not ms:
+                continue
+            e = {"ms": round(float(np.mean(ms)), 4), "ms_min": round(float(np.min(ms)), 4)}
+            if k in tiles:
+                e["tiles"] = tiles[k]
+                e["tflops"] = round(tiles[k] * FT / (e["ms"] * 1e-3) / 1e12, 2)
+                e["frac_of_bf16_peak"] = round(e["tflops"] / PEAK_BF16_TFLOPS, 4)
+                tot_tiles += tiles[k]
+            r["calls"][k] = e
+        r["tiles"] = tot_tiles
+        r["effective_tflops"] = round(tot_tiles * FT / (wall_ms * 1e-3) / 1e12, 2)
+        dense_tiles = int(C.tiles_dense(self.N).sum()) * self.Hq
+        r["sparsity_vs_causal"] = round(1.0 - tot_tiles / dense_tiles, 4)
+        return r
+
+
+def time_dense(x, heads, reps):
+    o = torch.empty_like(x.q)
+    B.minf_dense_attn(x.q, x.k, x.v, o, heads[:1])       # touch the code path once, one head
+    torch.cuda.synchronize()
+    t = Timer()
+    for _ in range(reps):
+        with t:
+            B.minf_dense_attn(x.q, x.k, x.v, o, heads)
+    torch.cuda.synchronize()
+    del o
+    return float(np.mean(t.ms()))
+
+
+def cpu_baseline(layer, budget_s=20.0):
+    """The CPU oracle, as it stands, on a bounded sample of the workload:
+    one Vertical-Slash head's index build in full, then attention on sampled
+    64-row query blocks of that head, until ~budget_s of CPU time is used."""
+    from oracle import minference_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    c, N = layer.cfg, layer.N
+    if layer.vs_heads:
+        h = layer.vs_heads[0]
+        Qh, Kh, Vh = layer.x.head_f64(h)
+        t0 = time.perf_counter()
+        Vi, Si, _, _ = O.vs_index(Qh, Kh, c["last_q"], c["nv"], c["ns"])
+        t_index = time.perf_counter() - t0
+        attend = lambda i0: O.vs_attention(Qh, Kh, Vh, Vi, Si, i0, i0 + 64)
+        n_index_heads = len(layer.vs_heads)
+    else:
+        h = (layer.a_heads or layer.bs_heads)[0]
+        Qh, Kh, Vh = layer.x.head_f64(h)
+        t_index, n_index_heads = 0.0, 0
+        if layer.a_heads:
+            attend = lambda i0: O.ashape_attention(Qh, Kh, Vh, c["n_init"], c["n_local"], i0, i0 + 64)
+        else:
+            t0 = time.perf_counter()
+            bi, bc, _ = O.bs_index(Qh, Kh, 64, c["topk"])
+            t_index, n_index_heads = time.perf_counter() - t0, len(layer.bs_heads)
+            attend = lambda i0: O.bs_attention(Qh, Kh, Vh, bi, bc, i0, i0 + 64)
+    NB = N // 64
+    rng = np.random.default_rng(7)
+    blocks, t_attn = [], 0.0
+    while t_attn + t_index < budget_s and len(blocks) < 64:
+        b = int(rng.integers(NB // 2, NB))
+        t0 = time.perf_counter()
+        attend(b * 64)
+        t_attn += time.perf_counter() - t0
+        blocks.append(b)
+    # linear extrapolation to the layer: index per head, attention per query block
+    n_blocks_layer = NB * layer.Hq
+    est_ms = (t_index * n_index_heads + t_attn / len(blocks) * n_blocks_layer) * 1e3
+    return {"value": round(est_ms, 1), "unit": "ms/layer (extrapolated)", "cores": int(cores),
+            "kind": "oracle",
+            "sample": (f"{layer.name}: oracle index build of 1 head ({t_index:.2f}s) + masked fp64 attention of "
+                       f"{len(blocks)} sampled 64-row query blocks of that head ({t_attn:.2f}s), "
+                       f"scaled to {n_index_heads} index heads and {n_blocks_layer} query blocks"),
+            "measured_s": round(t_index + t_attn, 2)}
+
+
+def read_traffic(kernel_tag):
+    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3
+    counter summary (profiles/*.txt, line 'traffic_bytes_per_launch[<tag>]: <n>')."""
+    pdir = os.path.join(ROOT, "profiles")
+    if not os.path.isdir(pdir):
+        return None
+    key = f"traffic_bytes_per_launch[{kernel_tag}]:"
+    for fn in sorted(os.listdir(pdir)):
+        if fn.endswith((".txt", ".md")):
+            for line in open(os.path.join(pdir, fn)):
+                if line.strip().startswith(key):
+                    try:
+                        return float(line.split(":", 1)[1].split()[0])
+                    except ValueError:
+                        return None
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--no-128k", action="store_true", help="skip the three 128K single-pattern layers")
+    ap.add_argument("--no-dense", action="store_true", help="skip the dense causal baseline")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (heads would shard across "
+              "GPUs without any exchange inside attention, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+    B.lib()
+    torch.cuda.set_device(0)
+
+    extra = {}
+    # ---- 128K single-pattern layers first (smaller; freed before the 1M layer)
+    if not a.no_128k and a.workload == "c4":
+        at128 = {}
+        for name in ("c1", "c2", "c3"):
+            L = Layer(name)
+            wall = L.run(max(a.steps, 3), a.warmup)
+            at128[name] = L.report(wall)
+            log(name, json.dumps(at128[name]))
+            if name == "c1" and not a.no_dense:
+                ms = time_dense(L.x, list(range(L.Hq)), 2)
+                dt = int(C.tiles_dense(L.N).sum()) * L.Hq
+                at128["dense"] = {"ms": round(ms, 3), "tiles": dt, "tflops": round(dt * FT / ms / 1e9, 2)}
+                log("dense 128K", json.dumps(at128["dense"]))
+            del L
+            torch.cuda.empty_cache()
+        if "dense" in at128:
+            for name in ("c1", "c2", "c3"):
+                at128[name]["speedup_vs_our_dense"] = round(at128["dense"]["ms"] / at128[name]["ms_per_layer"], 2)
+        extra["at_128k"] = at128
+
+    # ---- the timed workload
+    L = Layer(a.workload)
+    torch.cuda.synchronize()
+    wall = L.run(a.steps, a.warmup)
+    rep = L.report(wall)
+    log(a.workload, json.dumps(rep))
+
+    # dominant kernel = the attention call with the most tiles
+    dom = max((k for k in rep["calls"] if "tiles" in rep["calls"][k]), key=lambda k: rep["calls"][k]["ms"])
+    d = rep["calls"][dom]
+    roofline = {"bound": "mfma", "kernel": dom, "achieved": d["tflops"], "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(d["tflops"] / PEAK_BF16_TFLOPS, 4),
+                "traffic": read_traffic(f"{dom}:{a.workload}"),
+                "flops_per_launch": d["tiles"] * FT, "avg_launch_ms": d["ms"]}
+
+    if not a.no_dense:
+        if L.N > 262144:
+            heads = list(range(L.Hq // L.x.n_kv_heads))        # one KV group, scaled to the layer
+            ms = time_dense(L.x, heads, 1) * (L.Hq / len(heads))
+            note = f"1 rep of one KV group ({len(heads)} heads) x {L.Hq // len(heads)}, extrapolated"
+        else:
+            ms = time_dense(L.x, list(range(L.Hq)), 2)
+            note = "all heads, mean of 2 reps"
+        dt = int(C.tiles_dense(L.N).sum()) * L.Hq
+        extra["dense"] = {"ms": round(ms, 2), "tflops": round(dt * FT / ms / 1e9, 2), "how": note}
+        extra["speedup_vs_our_dense"] = round(ms / wall, 2)
+        log("dense", json.dumps(extra["dense"]))
+
+    cpu = None if a.no_cpu else cpu_baseline(L)
+    if cpu:
+        log("cpu_baseline", json.dumps(cpu))
+
+    c = L.cfg
+    out = {
+        "metric": "sparse-attn prefill ms/layer",
+        "value": round(wall, 4), "unit": "ms/layer", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": round(wall, 4), "higher_is_better": False, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{a.workload}: {c['name']}", "seq_len": L.N, "n_q_heads": L.Hq,
+                   "n_kv_heads": L.x.n_kv_heads, "head_dim": 128,
+                   "heads": {"vs": len(L.vs_heads), "bs": len(L.bs_heads), "ashape": len(L.a_heads)},
+                   "budgets": {k: c[k] for k in ("nv", "ns", "topk", "n_init", "n_local", "last_q") if k in c}},
+        "effective_tflops": rep["effective_tflops"],
+        "frac_of_bf16_peak": round(rep["effective_tflops"] / PEAK_BF16_TFLOPS, 4),
+        "breakdown": rep, "roofline": roofline, "cpu_baseline": cpu,
+    }
+    out.update(extra)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
