@@ -1,5 +1,5 @@
 // Device-side building blocks shared by the attention and index kernels:
-// MFMA vector types, LDS tile geometry, global -> register -> LDS tile staging.
+// MFMA vector types, the LDS tile layout and the global -> LDS tile fetch.
 #ifndef MINF_MFMA_TILE_H_
 #define MINF_MFMA_TILE_H_
 
@@ -9,19 +9,23 @@ namespace minf {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int D = 128;         // head dim
 constexpr int BQ = 64;         // query rows per wave (one paper block)
 constexpr int BK = 64;         // keys per tile
-constexpr int K_PITCH = 136;   // bf16 per LDS row of a K tile (256 B + 16 B pad)
-constexpr int VT_PITCH = 72;   // bf16 per LDS row of a V^T tile (128 B + 16 B pad)
-constexpr int K_TILE = BK * K_PITCH;      // 8704 elements
-constexpr int VT_TILE = D * VT_PITCH;     // 9216 elements
-constexpr int STAGE = K_TILE + VT_TILE;   // 17920 elements = 35840 B
-constexpr int KEY_NONE = 0x7fffffff;      // gathered column that must not be attended
-constexpr int VCAP = 1024;                // compacted vertical columns held in LDS per round
+constexpr int ROW_BYTES = 256; // one K or V row in LDS (128 bf16)
+constexpr int KEY_NONE = 0x7fffffff;   // gathered column that must not be attended
+
+// padded row-major K tile used by the Vertical-Slash estimate kernels
+constexpr int K_PITCH = 136;
+constexpr int K_TILE = BK * K_PITCH;
+
+#define MINF_GPTR(p) ((__attribute__((address_space(1))) void *)(p))
+#define MINF_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -31,96 +35,80 @@ __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 // (16t + 8h .. +7), which is what a B operand of the next MFMA must hold.
 __device__ inline int perm_row(int m) { return (m & ~12) | ((m & 4) << 1) | ((m & 8) >> 1); }
 
-struct WaveState {
-  bf16x8 q[2][8];     // Q fragments: [query half nb][k step]: Q[32nb + n][16ks + 8h ..]
-  f32x16 o[4][2];     // O^T accumulators: [d block][query half]
-  float m[2];         // running max of the scaled logits (log2 domain) of query 32nb + n
-  float l[2];         // this lane's share of the running row sum
-};
+// ---------------------------------------------------------------------------
+// LDS tile layout.  A K or V tile is ROWS rows of 256 B, row-major, with the
+// 16-byte chunk c of row r stored at chunk position c ^ (r & 15).  The XOR
+// spreads the 16 rows that a group of 16 lanes reads at the same column over
+// all 64 banks.  The tile is filled by direct global -> LDS loads
+// (global_load_lds_dwordx4: lane L's 16 bytes land at base + 16 L, so one
+// instruction fills one 1 KiB block = 4 rows and every lane fetches the chunk
+// that belongs at its position); no VGPRs and no LDS store instructions are
+// spent on staging.
+// ---------------------------------------------------------------------------
+__device__ inline int swz_byte(int r, int c16) { return r * ROW_BYTES + ((c16 ^ (r & 15)) << 4); }
 
-// Element mask of a tile, as seen by one wave (all fields wave-uniform).
-// A key is attended by query row i iff lo <= key < hi, key <= i and
-// (key < n_init or key + n_local > i).
-struct MaskP {
-  int q0;             // first query row of the wave's block
-  int lo, hi;
-  int n_init, n_local;
-};
-
-template <int NT>
-struct TileRegs {
-  uint4 k[1024 / NT];
-  uint4 v[1024 / NT];
-};
-
-// ---- tile fetch: global -> registers ------------------------------------
-// CONTIG: keys kbase .. kbase+63 (clamped to [0, N-1]; out-of-range keys are
-// masked by the caller).  Otherwise keys come from cols[0..63] in LDS
-// (KEY_NONE entries read row 0).
-template <int NT, bool CONTIG>
-__device__ inline void tile_issue(TileRegs<NT> &r, const bf16_t *kh, const bf16_t *vh, int64_t k_st,
-                                  int64_t v_st, int kbase, const int *cols, int N, int tid) {
+// Fetch ROWS rows into the tile at `tile` (LDS).  NW waves cooperate: wave w
+// issues blocks w, w + NW, ...  CONTIG: rows are keys kbase + r (clamped to
+// [0, N-1]; the caller masks out-of-range keys); otherwise keys come from
+// cols[r] in LDS (KEY_NONE reads row 0 and is masked by the caller).
+template <int NW, int ROWS, bool CONTIG>
+__device__ inline void dma_rows(const bf16_t *g, int64_t stride, int kbase, const int *cols, int N,
+                                char *tile, int wave, int lane) {
+  const int rl = lane >> 4, cpos = lane & 15;
 #pragma unroll
-  for (int i = 0; i < 1024 / NT; ++i) {
-    int c = tid + NT * i;
-    int row = c >> 4, col = c & 15;
+  for (int i = 0; i < ROWS / 4 / NW; ++i) {
+    const int blk = wave + NW * i;
+    const int r = 4 * blk + rl;
+    const int c = cpos ^ (r & 15);
     int key;
     if (CONTIG) {
-      key = min(max(kbase + row, 0), N - 1);
+      key = min(max(kbase + r, 0), N - 1);
     } else {
-      key = cols[row];
+      key = cols[r];
       key = key == KEY_NONE ? 0 : key;
     }
-    r.k[i] = *reinterpret_cast<const uint4 *>(kh + (int64_t)key * k_st + col * 8);
-  }
-#pragma unroll
-  for (int i = 0; i < 256 / NT; ++i) {
-    int u = tid + NT * i;
-    int kq = u >> 4, col = u & 15;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      int row = 4 * kq + j;
-      int key;
-      if (CONTIG) {
-        key = min(max(kbase + row, 0), N - 1);
-      } else {
-        key = cols[row];
-        key = key == KEY_NONE ? 0 : key;
-      }
-      r.v[4 * i + j] = *reinterpret_cast<const uint4 *>(vh + (int64_t)key * v_st + col * 8);
-    }
+    const bf16_t *src = g + (int64_t)key * stride + c * 8;
+    __builtin_amdgcn_global_load_lds(MINF_GPTR(src), MINF_LPTR(tile + blk * 1024), 16, 0, 0);
   }
 }
 
-// ---- tile store: registers -> LDS (K row-major, V transposed) -------------
-template <int NT>
-__device__ inline void tile_store(const TileRegs<NT> &r, bf16_t *ldsK, bf16_t *ldsVt, int tid) {
+// Per-lane byte offsets, inside a tile, of the MFMA A operands.
+//  K (S^T = K Q^T): lane (n = lane%32, h = lane/32), k step ks reads the 16 B
+//    chunk 2ks + h of row perm_row(n) (+ 32 rows per key block).
+//  V (O^T += V^T P^T): the operand wants 8 consecutive keys of one d column per
+//    lane while V rows hold d contiguous; ds_read_b64_tr_b16 transposes 4 keys
+//    x 16 d inside each group of 16 lanes: lane 4j + c of a group addresses
+//    V[key0 + j][d0 + 4c .. +3] and lane i receives V[key0 + 0..3][d0 + i].
+struct LaneOfs {
+  int k[8];        // [ks]
+  int v[4][2];     // [d block][half: keys +0..3 / +4..7], add (32mb + 16t) * 256
+};
+
+__device__ inline void lane_offsets(LaneOfs &lo, int lane) {
+  const int n = lane & 31, h = lane >> 5, prow = perm_row(n);
 #pragma unroll
-  for (int i = 0; i < 1024 / NT; ++i) {
-    int c = tid + NT * i;
-    int row = c >> 4, col = c & 15;
-    *reinterpret_cast<uint4 *>(ldsK + row * K_PITCH + col * 8) = r.k[i];
-  }
+  for (int ks = 0; ks < 8; ++ks) lo.k[ks] = swz_byte(prow, 2 * ks + h);
+  const int msub = (lane >> 4) & 1, l16 = lane & 15, j = l16 >> 2, c = l16 & 3;
 #pragma unroll
-  for (int i = 0; i < 256 / NT; ++i) {
-    int u = tid + NT * i;
-    int kq = u >> 4, col = u & 15;
-    const uint4 &a = r.v[4 * i + 0], &b = r.v[4 * i + 1], &c = r.v[4 * i + 2], &d = r.v[4 * i + 3];
-    const unsigned aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
-    const unsigned cw[4] = {c.x, c.y, c.z, c.w}, dw[4] = {d.x, d.y, d.z, d.w};
+  for (int db = 0; db < 4; ++db)
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      // dword w of a row holds d = 2w (low half) and 2w+1 (high half)
-      uint2 lo, hi;
-      lo.x = __builtin_amdgcn_perm(bw[w], aw[w], 0x05040100u);  // (a.lo, b.lo)
-      lo.y = __builtin_amdgcn_perm(dw[w], cw[w], 0x05040100u);  // (c.lo, d.lo)
-      hi.x = __builtin_amdgcn_perm(bw[w], aw[w], 0x07060302u);  // (a.hi, b.hi)
-      hi.y = __builtin_amdgcn_perm(dw[w], cw[w], 0x07060302u);
-      int dd = col * 8 + 2 * w;
-      *reinterpret_cast<uint2 *>(ldsVt + dd * VT_PITCH + 4 * kq) = lo;
-      *reinterpret_cast<uint2 *>(ldsVt + (dd + 1) * VT_PITCH + 4 * kq) = hi;
+    for (int half = 0; half < 2; ++half) {
+      const int key = 8 * h + 4 * half + j;
+      const int c16 = 4 * db + 2 * msub + (c >> 1);
+      lo.v[db][half] = swz_byte(key, c16) + (c & 1) * 8;
     }
-  }
+}
+
+__device__ inline bf16x8 lds_read_k(const char *tileK, int ofs) {
+  return *reinterpret_cast<const bf16x8 *>(tileK + ofs);
+}
+
+__device__ inline bf16x8 lds_read_vt(const char *tileV, int ofs0, int ofs1) {
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)MINF_LPTR(tileV + ofs0));
+  const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)MINF_LPTR(tileV + ofs1));
+  const s16x8 w = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, w);
 }
 
 }  // namespace minf
