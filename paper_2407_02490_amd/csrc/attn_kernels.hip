@@ -23,9 +23,15 @@
 //    costs the same as a contiguous one.  No mask tensor exists anywhere: the
 //    element mask is evaluated from (query row, key id) in registers, and only
 //    on tiles that can contain a masked element.
-//  * The running max is refreshed lazily: O and l are rescaled only when some
-//    row's max grew by more than 2^8 since the last refresh; exponentials are
-//    taken against the stale max (at most 2^8, harmless in fp32 / bf16).
+//  * Optimistic fixed reference: the exponent reference m of a row is taken
+//    once, from the row max of the first step the wave computes, and is never
+//    changed inside the hot loop: p = exp2(s - m) may then exceed 1, which fp32
+//    accumulators and bf16 P (fp32 exponent range) absorb up to 2^100.  The
+//    result is identical up to rounding because m cancels in O / l.  No
+//    per-step row max, no rescale of the 128 O registers, no branch on data.
+//    If a row sum ends up >= 2^100 or non-finite (logits that outgrow the first
+//    step's max by more than ~69 nats), the whole query block is redone with
+//    the exact two-pass scheme: pass 1 finds every row max, pass 2 accumulates.
 //  * A-shape / dense: a workgroup is 4 waves = 4 consecutive query blocks of
 //    one head; 64-key K/V tiles are staged once in LDS (double buffered) and
 //    shared by the 4 waves.  Block-Sparse / Vertical-Slash: tile lists differ
@@ -38,12 +44,12 @@ namespace minf {
 constexpr int VCAP = 1024;               // compacted vertical columns held in LDS per round
 constexpr int TILE_BYTES = 64 * ROW_BYTES;   // 64 rows of K or of V
 constexpr int HALF_BYTES = 32 * ROW_BYTES;   // 32 rows
-constexpr float RESCALE_LOG2 = 8.0f;     // refresh the running max when it grows by more than 2^8
+constexpr float L_LIMIT = 1.2676506e30f;  // 2^100: beyond it the optimistic pass is redone exactly
 
 struct WaveState {
   bf16x8 q[2][8];     // Q fragments: [query half nb][k step]: Q[32nb + n][16ks + 8h ..]
   f32x16 o[4][2];     // O^T accumulators: [d block][query half]
-  float m[2];         // reference max of the scaled logits (log2 domain) of query 32nb + n
+  float m[2];         // exponent reference of query 32nb + n (scaled logits, log2 domain)
   float l[2];         // this lane's share of the running row sum
 };
 
@@ -59,6 +65,8 @@ struct MaskP {
 #define MINF_WAIT_VMCNT(n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory")
 
 // ---- per-wave setup / epilogue ---------------------------------------------
+__device__ inline void set_reference(WaveState &st, int nb, float m) { st.m[nb] = m; }
+
 __device__ inline void wave_init(WaveState &st, const bf16_t *qh, int64_t q_st, int q0, int lane) {
   const int n = lane & 31, h = lane >> 5;
 #pragma unroll
@@ -66,7 +74,7 @@ __device__ inline void wave_init(WaveState &st, const bf16_t *qh, int64_t q_st, 
     const bf16_t *row = qh + (int64_t)(q0 + 32 * nb + n) * q_st + 8 * h;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) st.q[nb][ks] = *reinterpret_cast<const bf16x8 *>(row + 16 * ks);
-    st.m[nb] = -INFINITY;
+    set_reference(st, nb, 0.f);
     st.l[nb] = 0.f;
   }
 #pragma unroll
@@ -114,38 +122,46 @@ __device__ inline void wave_finish(WaveState &st, bf16_t *oh, int64_t o_st, int 
   }
 }
 
-// ---- one step of MB * 32 keys: S^T = K Q^T, mask, online softmax, O^T += V^T P^T
-// MODE 0: no element is masked.  MODE 1: contiguous keys kbase + idx, mask mp.
-// MODE 2: gathered keys cols[idx] (LDS), attended iff key <= query row.
+// ---- one step of MB * 32 keys: S^T = K Q^T, mask, p = exp2(c s - m), O^T += V^T P^T
+// The MFMA sequences appear exactly once per loop that calls this function;
+// everything that varies from step to step is a wave-uniform run-time flag that
+// only touches the logits, so the O accumulators keep one home for the whole
+// loop:
+//   mask_mode 0: no element is masked; 1: keys kbase + idx with the mask mp
+//   (GATHER: keys cols[idx] from LDS, attended iff key <= query row, always masked);
+//   first: take the reference m from this step's row max (optimistic pass).
+// PASS_MAX: only fold the row max into the reference candidates (st.l as scratch).
 // Register r of s[mb][nb] holds key index 32mb + 16(r/8) + 8h + (r%8) and
 // query 32nb + n (n = lane%32, h = lane/32).
-template <int MB, int MODE>
+enum { PASS_OPT = 0, PASS_MAX = 1, PASS_FIX = 2 };
+
+template <int MB, bool GATHER, int PASS>
 __device__ inline void step_compute(WaveState &st, const LaneOfs &lo, const char *tK, const char *tV,
-                                    int kbase, const int *cols, const MaskP &mp, float c_log2, int lane) {
+                                    int kbase, const int *cols, const MaskP &mp, int mask_mode, bool first,
+                                    float c_log2, int lane) {
   const int n = lane & 31, h = lane >> 5;
   f32x16 s[MB][2];
-#pragma unroll
-  for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[mb][nb][r] = 0.f;
-
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) {
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
       const bf16x8 a = lds_read_k(tK, lo.k[ks] + mb * HALF_BYTES);
-      s[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st.q[0][ks], s[mb][0], 0, 0, 0);
-      s[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st.q[1][ks], s[mb][1], 0, 0, 0);
+      if (ks == 0) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        s[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st.q[0][0], zero, 0, 0, 0);
+        s[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st.q[1][0], zero, 0, 0, 0);
+      } else {
+        s[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st.q[0][ks], s[mb][0], 0, 0, 0);
+        s[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st.q[1][ks], s[mb][1], 0, 0, 0);
+      }
     }
   }
 
-  if (MODE != 0) {
+  if (GATHER || mask_mode != 0) {
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
       int keys[16];
-      if (MODE == 2) {
+      if (GATHER) {
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
           const int4 a = *reinterpret_cast<const int4 *>(cols + 32 * mb + 16 * t + 8 * h);
@@ -161,40 +177,50 @@ __device__ inline void step_compute(WaveState &st, const LaneOfs &lo, const char
       for (int r = 0; r < 16; ++r) {
         const int key = keys[r];
         bool okk = true;
-        if (MODE == 1) okk = key >= mp.lo && key < mp.hi;
+        if (!GATHER) okk = key >= mp.lo && key < mp.hi;
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) {
           const int qi = mp.q0 + 32 * nb + n;
           bool ok = okk && key <= qi;
-          if (MODE == 1) ok = ok && (key < mp.n_init || key + mp.n_local > qi);
+          if (!GATHER) ok = ok && (key < mp.n_init || key + mp.n_local > qi);
           s[mb][nb][r] = ok ? s[mb][nb][r] : -INFINITY;
         }
       }
     }
   }
 
+  if (PASS == PASS_MAX) {
+    // st.l collects the row max of the raw logits (scaled after the pass)
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+      float mx = st.l[nb];
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[mb][nb][r]);
+      st.l[nb] = mx;
+    }
+    return;
+  }
+
+  if (PASS == PASS_OPT && first) {
+    // take the reference from this step's row max
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+      float mx = s[0][nb][0];
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[mb][nb][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32)) * c_log2;
+      set_reference(st, nb, mx == -INFINITY ? 0.f : mx);   // a row with no key yet: neutral reference
+    }
+  }
+
   bf16x8 p[2][MB][2];  // [nb][mb][t]
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb) {
-    float mx = s[0][nb][0];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[mb][nb][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32)) * c_log2;
-    // lazy refresh of the reference max (wave-uniform decision)
-    if (__builtin_amdgcn_ballot_w64(mx > st.m[nb] + RESCALE_LOG2) != 0) {
-      const float m_old = st.m[nb];
-      const float m_new = fmaxf(m_old, mx);
-      const float alpha = fast_exp2(m_old - (m_new == -INFINITY ? 0.f : m_new));
-      st.m[nb] = m_new;
-      st.l[nb] *= alpha;
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) st.o[db][nb][r] *= alpha;
-    }
-    const float m_use = st.m[nb] == -INFINITY ? 0.f : st.m[nb];
+    const float m_use = st.m[nb];
     float lsum = 0.f;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb)
@@ -245,14 +271,58 @@ __device__ inline int classify_step(int kbase, const MaskP &mp) {
   return full ? 1 : 2;
 }
 
-template <int MB>
-__device__ inline void contiguous_step(WaveState &st, const LaneOfs &lo, const char *tK, const char *tV,
-                                       int kbase, const MaskP &mp, float c_log2, int lane) {
+// has_ref (wave-uniform): whether the reference of the optimistic pass has been
+// taken; the first computed step takes it.
+template <int MB, int PASS>
+__device__ inline void contiguous_step(WaveState &st, bool &has_ref, const LaneOfs &lo, const char *tK,
+                                       const char *tV, int kbase, const MaskP &mp, float c_log2, int lane) {
   const int cls = classify_step<32 * MB>(kbase, mp);
-  if (cls == 1)
-    step_compute<MB, 0>(st, lo, tK, tV, kbase, nullptr, mp, c_log2, lane);
-  else if (cls == 2)
-    step_compute<MB, 1>(st, lo, tK, tV, kbase, nullptr, mp, c_log2, lane);
+  if (cls == 0) return;
+  const bool first = PASS == PASS_OPT && !has_ref;
+  has_ref = true;
+  step_compute<MB, false, PASS>(st, lo, tK, tV, kbase, nullptr, mp, cls == 2 ? 1 : 0, first, c_log2, lane);
+}
+
+template <int MB, int PASS>
+__device__ inline void gathered_step(WaveState &st, bool &has_ref, const LaneOfs &lo, const char *tK,
+                                     const char *tV, const int *cols, const MaskP &mp, float c_log2, int lane) {
+  const bool first = PASS == PASS_OPT && !has_ref;
+  has_ref = true;
+  step_compute<MB, true, PASS>(st, lo, tK, tV, 0, cols, mp, 1, first, c_log2, lane);
+}
+
+// After the optimistic pass: true (wave-uniform) if some row of the wave must be
+// redone exactly.
+__device__ inline bool needs_exact(const WaveState &st) {
+  bool bad = false;
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) {
+    const float l = st.l[nb] + __shfl_xor(st.l[nb], 32);
+    bad = bad || !(l < L_LIMIT);
+  }
+  return __builtin_amdgcn_ballot_w64(bad) != 0;
+}
+
+// Exact scheme, pass 1 set-up: zero reference, st.l collects the row max.
+__device__ inline void reset_for_max_pass(WaveState &st) {
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) { set_reference(st, nb, 0.f); st.l[nb] = -INFINITY; }
+#pragma unroll
+  for (int db = 0; db < 4; ++db)
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) st.o[db][nb][r] = 0.f;
+}
+
+// Exact scheme, between the passes: the row max becomes the reference.
+__device__ inline void finish_max_pass(WaveState &st, float c_log2) {
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) {
+    const float m = fmaxf(st.l[nb], __shfl_xor(st.l[nb], 32)) * c_log2;
+    set_reference(st, nb, m == -INFINITY ? 0.f : m);
+    st.l[nb] = 0.f;
+  }
 }
 
 // Work-item decode shared by the kernels: heads are taken in chunks of 4
@@ -282,6 +352,36 @@ __device__ inline void decode_item(int logical, int n_heads, int n_blk, int &slo
 // rows of one head per workgroup; shared, double-buffered 64-key K/V tiles.
 // LDS: 2 stages x (K 16 KiB + V 16 KiB).
 // ---------------------------------------------------------------------------
+struct AshapeCtx {
+  const bf16_t *kh, *vh;
+  int64_t k_st, v_st;
+  int N, T1, T, s2;
+  char *lds;
+  float c_log2;
+  __device__ inline int tile_base(int t) const { return t < T1 ? t * BK : s2 + (t - T1) * BK; }
+};
+
+template <int PASS>
+__device__ inline void ashape_pass(const AshapeCtx &c, WaveState &st, const LaneOfs &lo, const MaskP &mp,
+                                   int wave, int lane) {
+  auto fetch = [&](int t) {
+    char *stg = c.lds + (t & 1) * 2 * TILE_BYTES;
+    dma_rows<4, 64, true>(c.kh, c.k_st, c.tile_base(t), nullptr, c.N, stg, wave, lane);
+    dma_rows<4, 64, true>(c.vh, c.v_st, c.tile_base(t), nullptr, c.N, stg + TILE_BYTES, wave, lane);
+  };
+  bool has_ref = false;
+  fetch(0);
+  MINF_WAIT_VMCNT(0);
+  __syncthreads();
+  for (int t = 0; t < c.T; ++t) {
+    if (t + 1 < c.T) fetch(t + 1);
+    const char *stg = c.lds + (t & 1) * 2 * TILE_BYTES;
+    contiguous_step<2, PASS>(st, has_ref, lo, stg, stg + TILE_BYTES, c.tile_base(t), mp, c.c_log2, lane);
+    MINF_WAIT_VMCNT(0);
+    __syncthreads();
+  }
+}
+
 __global__ __launch_bounds__(256) void ashape_kernel(QKV x, HeadList hl, int n_init, int n_local,
                                                      Sched sched) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -291,7 +391,7 @@ __global__ __launch_bounds__(256) void ashape_kernel(QKV x, HeadList hl, int n_i
   int slot, sb;
   decode_item(logical, hl.n, NSB, slot, sb);
   const int head = hl.h[slot], kvh = head / x.group;
-  const bf16_t *qh = x.q + head * x.q_sh, *kh = x.k + kvh * x.k_sh, *vh = x.v + kvh * x.v_sh;
+  const bf16_t *qh = x.q + head * x.q_sh;
   bf16_t *oh = x.o + head * x.o_sh;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -312,23 +412,16 @@ __global__ __launch_bounds__(256) void ashape_kernel(QKV x, HeadList hl, int n_i
   int e1 = min(((n_init + BK - 1) / BK) * BK, wq1);
   int s2 = max(wq0 - n_local + 1, 0) / BK * BK;
   if (s2 <= e1) { s2 = 0; e1 = 0; }
-  const int T1 = e1 / BK, T = T1 + (wq1 - s2) / BK;
-  auto tile_base = [&](int t) { return t < T1 ? t * BK : s2 + (t - T1) * BK; };
-  auto fetch = [&](int t) {
-    char *stg = lds + (t & 1) * 2 * TILE_BYTES;
-    dma_rows<4, 64, true>(kh, x.k_st, tile_base(t), nullptr, x.N, stg, wave, lane);
-    dma_rows<4, 64, true>(vh, x.v_st, tile_base(t), nullptr, x.N, stg + TILE_BYTES, wave, lane);
-  };
+  AshapeCtx c;
+  c.kh = x.k + kvh * x.k_sh; c.vh = x.v + kvh * x.v_sh; c.k_st = x.k_st; c.v_st = x.v_st;
+  c.N = x.N; c.T1 = e1 / BK; c.T = c.T1 + (wq1 - s2) / BK; c.s2 = s2; c.lds = lds; c.c_log2 = x.c_log2;
 
-  fetch(0);
-  MINF_WAIT_VMCNT(0);
-  __syncthreads();
-  for (int t = 0; t < T; ++t) {
-    if (t + 1 < T) fetch(t + 1);
-    const char *stg = lds + (t & 1) * 2 * TILE_BYTES;
-    contiguous_step<2>(st, lo, stg, stg + TILE_BYTES, tile_base(t), mp, x.c_log2, lane);
-    MINF_WAIT_VMCNT(0);
-    __syncthreads();
+  ashape_pass<PASS_OPT>(c, st, lo, mp, wave, lane);
+  if (__syncthreads_or(needs_exact(st) ? 1 : 0)) {
+    reset_for_max_pass(st);
+    ashape_pass<PASS_MAX>(c, st, lo, mp, wave, lane);
+    finish_max_pass(st, x.c_log2);
+    ashape_pass<PASS_FIX>(c, st, lo, mp, wave, lane);
   }
   if (active) wave_finish(st, oh, x.o_st, q0, lds + wave * TILE_BYTES, lane);
 }
@@ -356,6 +449,45 @@ __device__ inline void fetch_step(const StepBuf &sb, int s, const bf16_t *kh, co
 // Block-Sparse: one wave per (head, query block); steps = halves of the listed
 // key blocks.
 // ---------------------------------------------------------------------------
+struct BsCtx {
+  const bf16_t *kh, *vh;
+  int64_t k_st, v_st;
+  int N, NB, cnt;
+  const int32_t *list;
+  StepBuf buf;
+  float c_log2;
+};
+
+template <int PASS>
+__device__ inline void bs_pass(const BsCtx &c, WaveState &st, const LaneOfs &lo, const MaskP &mp, int lane) {
+  // entries outside [0, NB) are skipped
+  auto next_valid = [&](int i) {
+    while (i < c.cnt) {
+      const int b = c.list[i];
+      if (b >= 0 && b < c.NB) break;
+      ++i;
+    }
+    return i;
+  };
+  bool has_ref = false;
+  int i = next_valid(0), half = 0, s = 0;
+  if (i < c.cnt) fetch_step<true>(c.buf, 0, c.kh, c.vh, c.k_st, c.v_st, c.list[i] * BK, nullptr, c.N, lane);
+  while (i < c.cnt) {
+    const int kbase = c.list[i] * BK + 32 * half;
+    int i2 = i;
+    const int half2 = half ^ 1;
+    if (half == 1) i2 = next_valid(i + 1);
+    if (i2 < c.cnt) {
+      fetch_step<true>(c.buf, s ^ 1, c.kh, c.vh, c.k_st, c.v_st, c.list[i2] * BK + 32 * half2, nullptr, c.N, lane);
+      MINF_WAIT_VMCNT(16);
+    } else {
+      MINF_WAIT_VMCNT(0);
+    }
+    contiguous_step<1, PASS>(st, has_ref, lo, c.buf.k(s), c.buf.v(s), kbase, mp, c.c_log2, lane);
+    i = i2; half = half2; s ^= 1;
+  }
+}
+
 __global__ __launch_bounds__(64) void bs_kernel(QKV x, HeadList hl, const int32_t *blk_idx,
                                                 const int32_t *blk_cnt, int topk, Sched sched) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -365,7 +497,7 @@ __global__ __launch_bounds__(64) void bs_kernel(QKV x, HeadList hl, const int32_
   int slot, b;
   decode_item(logical, hl.n, NB, slot, b);
   const int head = hl.h[slot], kvh = head / x.group;
-  const bf16_t *qh = x.q + head * x.q_sh, *kh = x.k + kvh * x.k_sh, *vh = x.v + kvh * x.v_sh;
+  const bf16_t *qh = x.q + head * x.q_sh;
   bf16_t *oh = x.o + head * x.o_sh;
   const int lane = threadIdx.x;
   const int q0 = b * BQ;
@@ -376,33 +508,18 @@ __global__ __launch_bounds__(64) void bs_kernel(QKV x, HeadList hl, const int32_
   lane_offsets(lo, lane);
   MaskP mp;
   mp.q0 = q0; mp.lo = 0; mp.hi = x.N; mp.n_init = KEY_NONE; mp.n_local = 1;
-  const StepBuf buf{lds};
+  BsCtx c;
+  c.kh = x.k + kvh * x.k_sh; c.vh = x.v + kvh * x.v_sh; c.k_st = x.k_st; c.v_st = x.v_st;
+  c.N = x.N; c.NB = NB; c.buf = StepBuf{lds}; c.c_log2 = x.c_log2;
+  c.list = blk_idx + ((int64_t)slot * NB + b) * topk;
+  c.cnt = min(max(blk_cnt[(int64_t)slot * NB + b], 0), topk);
 
-  const int32_t *list = blk_idx + ((int64_t)slot * NB + b) * topk;
-  const int cnt = min(max(blk_cnt[(int64_t)slot * NB + b], 0), topk);
-  // step index u = 2 * (list position) + half; entries outside [0, NB) are skipped
-  auto next_valid = [&](int i) {
-    while (i < cnt) {
-      const int c = list[i];
-      if (c >= 0 && c < NB) break;
-      ++i;
-    }
-    return i;
-  };
-  int i = next_valid(0), half = 0, s = 0;
-  if (i < cnt) fetch_step<true>(buf, 0, kh, vh, x.k_st, x.v_st, list[i] * BK, nullptr, x.N, lane);
-  while (i < cnt) {
-    const int kbase = list[i] * BK + 32 * half;
-    int i2 = i, half2 = half ^ 1;
-    if (half == 1) i2 = next_valid(i + 1);
-    if (i2 < cnt) {
-      fetch_step<true>(buf, s ^ 1, kh, vh, x.k_st, x.v_st, list[i2] * BK + 32 * half2, nullptr, x.N, lane);
-      MINF_WAIT_VMCNT(16);
-    } else {
-      MINF_WAIT_VMCNT(0);
-    }
-    contiguous_step<1>(st, lo, buf.k(s), buf.v(s), kbase, mp, x.c_log2, lane);
-    i = i2; half = half2; s ^= 1;
+  bs_pass<PASS_OPT>(c, st, lo, mp, lane);
+  if (needs_exact(st)) {
+    reset_for_max_pass(st);
+    bs_pass<PASS_MAX>(c, st, lo, mp, lane);
+    finish_max_pass(st, x.c_log2);
+    bs_pass<PASS_FIX>(c, st, lo, mp, lane);
   }
   wave_finish(st, oh, x.o_st, q0, lds, lane);
 }
@@ -415,6 +532,99 @@ __global__ __launch_bounds__(64) void bs_kernel(QKV x, HeadList hl, const int32_
 //           run, compacted (ballot + prefix count) into LDS and gathered 32 at
 //           a time.
 // ---------------------------------------------------------------------------
+struct VsCtx {
+  const bf16_t *kh, *vh;
+  int64_t k_st, v_st;
+  int N, q0, n_v, n_c;
+  const int32_t *vlist;
+  const int2 *runs;
+  const uint32_t *bits;
+  StepBuf buf;
+  int *cols;
+  float c_log2;
+};
+
+template <int PASS>
+__device__ inline void vs_pass(const VsCtx &c, WaveState &st, const LaneOfs &lo, MaskP mp, int lane) {
+  const int q0 = c.q0;
+  bool has_ref = false;
+  // ---- phase A: slash runs -------------------------------------------------
+  int iv = 0, ks = 0, ke = 0, pos = 0;   // run index, clipped key range [ks, ke), next step start
+  auto next_run_step = [&](int &kbase, int &rlo, int &rhi) -> bool {
+    while (true) {
+      if (pos < ke) {
+        kbase = pos; rlo = ks; rhi = ke;
+        pos += 32;
+        return true;
+      }
+      if (iv >= c.n_c) return false;
+      const int2 r = c.runs[iv];
+      if (r.x > q0) { iv = c.n_c; return false; }   // runs ascend: no later run reaches key >= 0
+      ++iv;
+      ks = max(q0 - r.y + 1, 0);
+      ke = min(q0 - r.x + 1, c.N);
+      pos = ks;
+    }
+  };
+  int s = 0;
+  int kb, rlo, rhi, kb2 = 0, rlo2 = 0, rhi2 = 0;
+  bool have = next_run_step(kb, rlo, rhi);
+  if (have) fetch_step<true>(c.buf, 0, c.kh, c.vh, c.k_st, c.v_st, kb, nullptr, c.N, lane);
+  while (have) {
+    const bool have2 = next_run_step(kb2, rlo2, rhi2);
+    if (have2) {
+      fetch_step<true>(c.buf, s ^ 1, c.kh, c.vh, c.k_st, c.v_st, kb2, nullptr, c.N, lane);
+      MINF_WAIT_VMCNT(16);
+    } else {
+      MINF_WAIT_VMCNT(0);
+    }
+    mp.lo = rlo; mp.hi = rhi;
+    contiguous_step<1, PASS>(st, has_ref, lo, c.buf.k(s), c.buf.v(s), kb, mp, c.c_log2, lane);
+    have = have2; kb = kb2; rlo = rlo2; rhi = rhi2; s ^= 1;
+  }
+
+  // ---- phase B: verticals ----------------------------------------------------
+  const int qlast = q0 + BQ - 1;
+  int *cols = c.cols;
+  int vpos = 0;                       // next entry of vlist to examine
+  while (vpos < c.n_v) {
+    // compact up to VCAP columns into cols[]
+    int ncol = 0;
+    while (vpos < c.n_v && ncol <= VCAP - 64) {
+      const int i = vpos + lane;
+      const int v = i < c.n_v ? c.vlist[i] : KEY_NONE;
+      bool ok = v <= qlast && v >= 0;
+      if (ok) {
+        const int t = q0 - v + 64;     // bit index of offset q0 - v, in [1, q0 + 64]
+        ok = ((c.bits[t >> 5] >> (t & 31)) & 1u) == 0u;
+      }
+      const unsigned long long bal = __builtin_amdgcn_ballot_w64(ok);
+      const int before = __builtin_popcountll(bal & ((1ull << lane) - 1ull));
+      if (ok) cols[ncol + before] = v;
+      ncol += __builtin_popcountll(bal);
+      vpos += 64;
+      // the list ascends: once a whole chunk is past the block nothing follows
+      if (__shfl(v, 0) > qlast) { vpos = c.n_v; break; }
+    }
+    if (ncol == 0) continue;
+    const int nstep = (ncol + 31) / 32;
+    if (lane + ncol < nstep * 32) cols[ncol + lane] = KEY_NONE;   // pad the last step
+    __syncthreads();                   // cols[] visible to every lane; earlier vector loads drained
+    fetch_step<false>(c.buf, s, c.kh, c.vh, c.k_st, c.v_st, 0, cols, c.N, lane);
+    for (int t = 0; t < nstep; ++t) {
+      if (t + 1 < nstep) {
+        fetch_step<false>(c.buf, s ^ 1, c.kh, c.vh, c.k_st, c.v_st, 0, cols + (t + 1) * 32, c.N, lane);
+        MINF_WAIT_VMCNT(16);
+      } else {
+        MINF_WAIT_VMCNT(0);
+      }
+      gathered_step<1, PASS>(st, has_ref, lo, c.buf.k(s), c.buf.v(s), cols + t * 32, mp, c.c_log2, lane);
+      s ^= 1;
+    }
+    __syncthreads();                   // every lane is done with cols[] before the next round refills it
+  }
+}
+
 __global__ __launch_bounds__(64) void vs_kernel(QKV x, HeadList hl, const int32_t *v_idx,
                                                 const int32_t *cover, const uint32_t *cover_bits,
                                                 const int32_t *counts, int nv, int ns, int cover_words,
@@ -426,19 +636,20 @@ __global__ __launch_bounds__(64) void vs_kernel(QKV x, HeadList hl, const int32_
   int slot, b;
   decode_item(logical, hl.n, NB, slot, b);
   const int head = hl.h[slot], kvh = head / x.group;
-  const bf16_t *qh = x.q + head * x.q_sh, *kh = x.k + kvh * x.k_sh, *vh = x.v + kvh * x.v_sh;
+  const bf16_t *qh = x.q + head * x.q_sh;
   bf16_t *oh = x.o + head * x.o_sh;
   const int lane = threadIdx.x;
   const int q0 = b * BQ;
 
-  const StepBuf buf{lds};
-  int *cols = reinterpret_cast<int *>(lds + 4 * HALF_BYTES);   // [VCAP + 64]
-
-  const int n_v = min(max(counts[slot * 4 + 0], 0), nv);
-  const int n_c = min(max(counts[slot * 4 + 2], 0), ns);
-  const int32_t *vlist = v_idx + (int64_t)slot * nv;
-  const int2 *runs = reinterpret_cast<const int2 *>(cover) + (int64_t)slot * ns;
-  const uint32_t *bits = cover_bits + (int64_t)slot * cover_words;
+  VsCtx c;
+  c.kh = x.k + kvh * x.k_sh; c.vh = x.v + kvh * x.v_sh; c.k_st = x.k_st; c.v_st = x.v_st;
+  c.N = x.N; c.q0 = q0; c.buf = StepBuf{lds}; c.c_log2 = x.c_log2;
+  c.cols = reinterpret_cast<int *>(lds + 4 * HALF_BYTES);   // [VCAP + 64]
+  c.n_v = min(max(counts[slot * 4 + 0], 0), nv);
+  c.n_c = min(max(counts[slot * 4 + 2], 0), ns);
+  c.vlist = v_idx + (int64_t)slot * nv;
+  c.runs = reinterpret_cast<const int2 *>(cover) + (int64_t)slot * ns;
+  c.bits = cover_bits + (int64_t)slot * cover_words;
 
   WaveState st;
   wave_init(st, qh, x.q_st, q0, lane);
@@ -447,79 +658,12 @@ __global__ __launch_bounds__(64) void vs_kernel(QKV x, HeadList hl, const int32_
   MaskP mp;
   mp.q0 = q0; mp.n_init = KEY_NONE; mp.n_local = 1; mp.lo = 0; mp.hi = 0;
 
-  // ---- phase A: slash runs -------------------------------------------------
-  int iv = 0, ks = 0, ke = 0, pos = 0;   // run index, clipped key range [ks, ke), next step start
-  auto next_run_step = [&](int &kbase, int &rlo, int &rhi) -> bool {
-    while (true) {
-      if (pos < ke) {
-        kbase = pos; rlo = ks; rhi = ke;
-        pos += 32;
-        return true;
-      }
-      if (iv >= n_c) return false;
-      const int2 r = runs[iv];
-      if (r.x > q0) { iv = n_c; return false; }   // runs ascend: no later run reaches key >= 0
-      ++iv;
-      ks = max(q0 - r.y + 1, 0);
-      ke = min(q0 - r.x + 1, x.N);
-      pos = ks;
-    }
-  };
-  int s = 0;
-  int kb, rlo, rhi, kb2, rlo2, rhi2;
-  bool have = next_run_step(kb, rlo, rhi);
-  if (have) fetch_step<true>(buf, 0, kh, vh, x.k_st, x.v_st, kb, nullptr, x.N, lane);
-  while (have) {
-    const bool have2 = next_run_step(kb2, rlo2, rhi2);
-    if (have2) {
-      fetch_step<true>(buf, s ^ 1, kh, vh, x.k_st, x.v_st, kb2, nullptr, x.N, lane);
-      MINF_WAIT_VMCNT(16);
-    } else {
-      MINF_WAIT_VMCNT(0);
-    }
-    mp.lo = rlo; mp.hi = rhi;
-    contiguous_step<1>(st, lo, buf.k(s), buf.v(s), kb, mp, x.c_log2, lane);
-    have = have2; kb = kb2; rlo = rlo2; rhi = rhi2; s ^= 1;
-  }
-
-  // ---- phase B: verticals ----------------------------------------------------
-  const int qlast = q0 + BQ - 1;
-  int vpos = 0;                       // next entry of vlist to examine
-  while (vpos < n_v) {
-    // compact up to VCAP columns into cols[]
-    int ncol = 0;
-    while (vpos < n_v && ncol <= VCAP - 64) {
-      const int i = vpos + lane;
-      const int v = i < n_v ? vlist[i] : KEY_NONE;
-      bool ok = v <= qlast && v >= 0;
-      if (ok) {
-        const int t = q0 - v + 64;     // bit index of offset q0 - v, in [1, q0 + 64]
-        ok = ((bits[t >> 5] >> (t & 31)) & 1u) == 0u;
-      }
-      const unsigned long long bal = __builtin_amdgcn_ballot_w64(ok);
-      const int before = __builtin_popcountll(bal & ((1ull << lane) - 1ull));
-      if (ok) cols[ncol + before] = v;
-      ncol += __builtin_popcountll(bal);
-      vpos += 64;
-      // the list ascends: once a whole chunk is past the block nothing follows
-      if (__shfl(v, 0) > qlast) { vpos = n_v; break; }
-    }
-    if (ncol == 0) continue;
-    const int nstep = (ncol + 31) / 32;
-    if (lane + ncol < nstep * 32) cols[ncol + lane] = KEY_NONE;   // pad the last step
-    __syncthreads();                   // cols[] visible to every lane; earlier vector loads drained
-    fetch_step<false>(buf, s, kh, vh, x.k_st, x.v_st, 0, cols, x.N, lane);
-    for (int t = 0; t < nstep; ++t) {
-      if (t + 1 < nstep) {
-        fetch_step<false>(buf, s ^ 1, kh, vh, x.k_st, x.v_st, 0, cols + (t + 1) * 32, x.N, lane);
-        MINF_WAIT_VMCNT(16);
-      } else {
-        MINF_WAIT_VMCNT(0);
-      }
-      step_compute<1, 2>(st, lo, buf.k(s), buf.v(s), 0, cols + t * 32, mp, x.c_log2, lane);
-      s ^= 1;
-    }
-    __syncthreads();                   // every lane is done with cols[] before the next round refills it
+  vs_pass<PASS_OPT>(c, st, lo, mp, lane);
+  if (needs_exact(st)) {
+    reset_for_max_pass(st);
+    vs_pass<PASS_MAX>(c, st, lo, mp, lane);
+    finish_max_pass(st, x.c_log2);
+    vs_pass<PASS_FIX>(c, st, lo, mp, lane);
   }
   wave_finish(st, oh, x.o_st, q0, lds, lane);
 }

@@ -47,14 +47,55 @@ __device__ inline int perm_row(int m) { return (m & ~12) | ((m & 4) << 1) | ((m 
 // ---------------------------------------------------------------------------
 __device__ inline int swz_byte(int r, int c16) { return r * ROW_BYTES + ((c16 ^ (r & 15)) << 4); }
 
+// One direct global -> LDS load of 16 bytes per lane: lane L's bytes land at
+// LDS byte address lds_addr + 16 L (lds_addr wave-uniform).  Written as inline
+// assembly so that the compiler does not serialise later LDS reads of OTHER
+// tiles behind it; completion is awaited explicitly with s_waitcnt vmcnt.
+__device__ inline void dma16(const void *g, unsigned lds_addr) {
+  const unsigned a = __builtin_amdgcn_readfirstlane(lds_addr);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :: "v"(g), "s"(a) : "memory");
+}
+
+__device__ inline unsigned lds_addr_of(const void *p) {
+  return (unsigned)(size_t)(__attribute__((address_space(3))) const char *)p;
+}
+
+// Same, with the address split into a wave-uniform 64-bit base (SGPR pair) and a
+// per-lane 32-bit byte offset: no vector ALU work per load.
+__device__ inline void dma16_su(const void *ubase, unsigned voff, unsigned lds_addr) {
+  const unsigned long long b = (unsigned long long)ubase;
+  const unsigned blo = __builtin_amdgcn_readfirstlane((unsigned)b);
+  const unsigned bhi = __builtin_amdgcn_readfirstlane((unsigned)(b >> 32));
+  const unsigned long long bs = ((unsigned long long)bhi << 32) | blo;
+  const unsigned a = __builtin_amdgcn_readfirstlane(lds_addr);
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(voff), "s"(bs), "s"(a) : "memory");
+}
+
 // Fetch ROWS rows into the tile at `tile` (LDS).  NW waves cooperate: wave w
-// issues blocks w, w + NW, ...  CONTIG: rows are keys kbase + r (clamped to
-// [0, N-1]; the caller masks out-of-range keys); otherwise keys come from
-// cols[r] in LDS (KEY_NONE reads row 0 and is masked by the caller).
+// issues blocks w, w + NW, ...  CONTIG: rows are keys kbase + r; rows outside
+// [0, N) are clamped (the caller masks them); a step that lies wholly inside
+// [0, N) -- the common case -- takes the uniform-base form.  Otherwise keys come
+// from cols[r] in LDS (KEY_NONE reads row 0 and is masked by the caller).
+// stride * 2 * ROWS must fit 32 bits.
 template <int NW, int ROWS, bool CONTIG>
 __device__ inline void dma_rows(const bf16_t *g, int64_t stride, int kbase, const int *cols, int N,
                                 char *tile, int wave, int lane) {
   const int rl = lane >> 4, cpos = lane & 15;
+  const unsigned base = lds_addr_of(tile);
+  if (CONTIG && kbase >= 0 && kbase + ROWS <= N) {
+    const bf16_t *ubase = g + (int64_t)kbase * stride;
+    const unsigned row_bytes = (unsigned)stride * 2u;
+#pragma unroll
+    for (int i = 0; i < ROWS / 4 / NW; ++i) {
+      const int blk = wave + NW * i;
+      const int r = 4 * blk + rl;
+      const int c = cpos ^ (r & 15);
+      dma16_su(ubase, (unsigned)r * row_bytes + (unsigned)c * 16u, base + blk * 1024);
+    }
+    return;
+  }
 #pragma unroll
   for (int i = 0; i < ROWS / 4 / NW; ++i) {
     const int blk = wave + NW * i;
@@ -67,8 +108,7 @@ __device__ inline void dma_rows(const bf16_t *g, int64_t stride, int kbase, cons
       key = cols[r];
       key = key == KEY_NONE ? 0 : key;
     }
-    const bf16_t *src = g + (int64_t)key * stride + c * 8;
-    __builtin_amdgcn_global_load_lds(MINF_GPTR(src), MINF_LPTR(tile + blk * 1024), 16, 0, 0);
+    dma16(g + (int64_t)key * stride + c * 8, base + blk * 1024);
   }
 }
 

@@ -25,6 +25,7 @@ minf_status check_qkv(const minf_qkv *x, bool need_v_o) {
     for (int i = 0; i < 3; ++i)
       if (s[t][i] < 0 || s[t][i] % 8 != 0) return MINF_ERR_SHAPE;
     if (s[t][2] < x->head_dim) return MINF_ERR_SHAPE;
+    if (s[t][2] > (int64_t)1 << 24) return MINF_ERR_SHAPE;   // 64 rows * stride * 2 B must fit 32 bits
   }
   const void *p[4] = {x->q, x->k, x->v, x->o};
   for (int t = 0; t < (need_v_o ? 4 : 2); ++t)

@@ -159,3 +159,33 @@ def test_bad_arguments_are_rejected_before_launch(B):
         B.minf_dense_attn(q[:, :100], k[:, :100], v[:, :100], o[:, :100], [0])   # N % 64 != 0
     assert e.value.status == 2
     assert (o == 0).all()
+
+
+def test_exact_two_pass_fallback(B):
+    """Logits that outgrow the first step's row max by far more than 2^100
+    overflow the optimistic fixed-reference pass; the kernels must detect it
+    and redo the query block with the exact two-pass scheme."""
+    N = 1024
+    q, k, v = random_qkv(21, 2, 1, N)
+    k = k.clone()
+    k[:, 700:] *= 60.0                      # late keys: logits of +-100s of nats
+    # dense / A-shape
+    o = run_heads(B.minf_dense_attn, q, k, v, [0, 1])
+    for h in (0, 1):
+        want = O.dense_attention(to_f64(q[h]), to_f64(k[0]), to_f64(v[0]))
+        assert_close_rows(o[h], want, f"fallback dense head {h}")
+    # Block-Sparse with every block kept
+    NB = N // 64
+    idx = np.tile(np.arange(NB), (NB, 1))
+    cnt = np.arange(1, NB + 1)
+    idx = np.where(idx < cnt[:, None], idx, -1)
+    dev = B.bs_index_from_host(np.stack([idx, idx]), np.stack([cnt, cnt]))
+    o = run_heads(B.minf_bs_attn, q, k, v, [0, 1], dev)
+    assert_close_rows(o[1], O.dense_attention(to_f64(q[1]), to_f64(k[0]), to_f64(v[0])), "fallback bs")
+    # Vertical-Slash: a local band plus verticals inside the scaled region
+    Vl, Sl = [5, 710, 800, 1000], list(range(0, 96)) + [300]
+    dev = B.vs_index_from_host([Vl, Vl], [Sl, Sl], N)
+    o = run_heads(B.minf_vs_attn, q, k, v, [0, 1], dev)
+    for h in (0, 1):
+        want = O.vs_attention(to_f64(q[h]), to_f64(k[0]), to_f64(v[0]), Vl, Sl, Bm=64)
+        assert_close_rows(o[h], want, f"fallback vs head {h}")
