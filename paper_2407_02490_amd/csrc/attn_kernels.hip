@@ -258,6 +258,166 @@ __device__ inline void step_compute(WaveState &st, const LaneOfs &lo, const char
       }
 }
 
+// ---- the same arithmetic as step_compute, split into its three phases so that a
+// loop can overlap phases of neighbouring tiles (software pipelining) ---------
+template <int MB>
+__device__ inline void qk_tile(f32x16 (&s)[MB][2], const WaveState &st, const LaneOfs &lo, const char *tK) {
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      const bf16x8 a = lds_read_k(tK, lo.k[ks] + mb * HALF_BYTES);
+      if (ks == 0) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        s[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st.q[0][0], zero, 0, 0, 0);
+        s[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st.q[1][0], zero, 0, 0, 0);
+      } else {
+        s[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st.q[0][ks], s[mb][0], 0, 0, 0);
+        s[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, st.q[1][ks], s[mb][1], 0, 0, 0);
+      }
+    }
+  }
+}
+
+// Rare path on fresh logits of a contiguous tile: element mask and / or taking
+// the exponent reference from this tile's row max.
+template <int MB>
+__device__ inline void special_tile(f32x16 (&s)[MB][2], WaveState &st, int kbase, const MaskP &mp,
+                                    bool need_mask, bool first, float c_log2, int lane) {
+  const int n = lane & 31, h = lane >> 5;
+  if (need_mask) {
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = kbase + 32 * mb + 16 * (r >> 3) + 8 * h + (r & 7);
+        const bool okk = key >= mp.lo && key < mp.hi;
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb) {
+          const int qi = mp.q0 + 32 * nb + n;
+          const bool ok = okk && key <= qi && (key < mp.n_init || key + mp.n_local > qi);
+          s[mb][nb][r] = ok ? s[mb][nb][r] : -INFINITY;
+        }
+      }
+  }
+  if (first) {
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+      float mx = s[0][nb][0];
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[mb][nb][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32)) * c_log2;
+      set_reference(st, nb, mx == -INFINITY ? 0.f : mx);
+    }
+  }
+}
+
+template <int MB>
+__device__ inline void softmax_tile(bf16x8 (&p)[2][MB][2], WaveState &st, const f32x16 (&s)[MB][2],
+                                    float c_log2) {
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) {
+    const float m_use = st.m[nb];
+    float lsum = 0.f;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        float e[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          e[i] = fast_exp2(fmaf(s[mb][nb][8 * t + i], c_log2, -m_use));
+          lsum += e[i];
+        }
+        bf16x8 pk;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const f32x2 two = {e[2 * i], e[2 * i + 1]};
+          const bf16x2 b2 = __builtin_convertvector(two, bf16x2);
+          pk[2 * i] = b2[0];
+          pk[2 * i + 1] = b2[1];
+        }
+        p[nb][mb][t] = pk;
+      }
+    st.l[nb] += lsum;
+  }
+}
+
+template <int MB>
+__device__ inline void pv_tile(WaveState &st, const LaneOfs &lo, const char *tV, const bf16x8 (&p)[2][MB][2]) {
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int db = 0; db < 4; ++db) {
+        const int base = (32 * mb + 16 * t) * ROW_BYTES;
+        const bf16x8 a = lds_read_vt(tV, lo.v[db][0] + base, lo.v[db][1] + base);
+        st.o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p[0][mb][t], st.o[db][0], 0, 0, 0);
+        st.o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p[1][mb][t], st.o[db][1], 0, 0, 0);
+      }
+}
+
+// QK of one 64-key tile fused with the softmax of the previous tile, interleaved
+// by hand: 8 rounds of {4 MFMAs of k-step ks; one eighth of the exp work; LDS
+// reads of k-step ks+1}.  The vector ALU work of a round (about 30 instructions)
+// runs in the shadow of the round's 4 MFMAs (128 cycles).  sched_barrier(0)
+// keeps the compiler from regrouping the rounds.
+__device__ inline void fused_qk_softmax(f32x16 (&s_nxt)[2][2], bf16x8 (&p)[2][2][2], WaveState &st,
+                                        const f32x16 (&s_cur)[2][2], const LaneOfs &lo, const char *tK,
+                                        float c_log2) {
+  const float m0 = st.m[0], m1 = st.m[1];
+  float lsum0 = 0.f, lsum1 = 0.f;
+  bf16x8 a0 = lds_read_k(tK, lo.k[0]), a1 = lds_read_k(tK, lo.k[0] + HALF_BYTES);
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    const bf16x8 c0 = a0, c1 = a1;
+    if (ks + 1 < 8) {
+      a0 = lds_read_k(tK, lo.k[ks + 1]);
+      a1 = lds_read_k(tK, lo.k[ks + 1] + HALF_BYTES);
+    }
+    if (ks == 0) {
+      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      s_nxt[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c0, st.q[0][0], zero, 0, 0, 0);
+      s_nxt[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c0, st.q[1][0], zero, 0, 0, 0);
+      s_nxt[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c1, st.q[0][0], zero, 0, 0, 0);
+      s_nxt[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c1, st.q[1][0], zero, 0, 0, 0);
+    } else {
+      s_nxt[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c0, st.q[0][ks], s_nxt[0][0], 0, 0, 0);
+      s_nxt[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c0, st.q[1][ks], s_nxt[0][1], 0, 0, 0);
+      s_nxt[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c1, st.q[0][ks], s_nxt[1][0], 0, 0, 0);
+      s_nxt[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c1, st.q[1][ks], s_nxt[1][1], 0, 0, 0);
+    }
+    // softmax slice ks of the previous tile: (nb, mb, t) = (ks / 4, (ks / 2) % 2, ks % 2)
+    const int nb = ks >> 2, mb = (ks >> 1) & 1, t = ks & 1;
+    const float m_use = nb == 0 ? m0 : m1;
+    float e[8];
+    float part = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      e[i] = fast_exp2(fmaf(s_cur[mb][nb][8 * t + i], c_log2, -m_use));
+      part += e[i];
+    }
+    if (nb == 0) lsum0 += part; else lsum1 += part;
+    // keep this round's adds in this round (they would otherwise sink to the end of the block)
+    asm volatile("" : "+v"(lsum0), "+v"(lsum1));
+    bf16x8 pk;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const f32x2 two = {e[2 * i], e[2 * i + 1]};
+      const bf16x2 b2 = __builtin_convertvector(two, bf16x2);
+      pk[2 * i] = b2[0];
+      pk[2 * i + 1] = b2[1];
+    }
+    p[nb][mb][t] = pk;
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  st.l[0] += lsum0;
+  st.l[1] += lsum1;
+}
+
 // Classify a contiguous step [kbase, kbase + W) for the wave whose rows are
 // q0 .. q0+63.  0 = nothing to attend (skip), 1 = fully attended (no element
 // mask needed), 2 = partially attended.
@@ -382,6 +542,75 @@ __device__ inline void ashape_pass(const AshapeCtx &c, WaveState &st, const Lane
   }
 }
 
+// Optimistic pass, software pipelined: while the vector ALU turns the logits of
+// tile t into P, the matrix cores already form the logits of tile t+1; then
+// P V of tile t.  K therefore runs one tile ahead of V through the two LDS
+// buffers of each: at the top of iteration t the wave issues the loads of
+// K(t+2) and V(t+1), which have a whole iteration to land.
+struct AshapePipe {
+  const AshapeCtx &c;
+  WaveState &st;
+  const LaneOfs &lo;
+  const MaskP &mp;
+  int wave, lane;
+  bool has_ref;
+  int cls_cur;
+
+  __device__ inline char *kbuf(int t) const { return c.lds + (t & 1) * TILE_BYTES; }
+  __device__ inline char *vbuf(int t) const { return c.lds + (2 + (t & 1)) * TILE_BYTES; }
+  __device__ inline void fetch_k(int t) const {
+    dma_rows<4, 64, true>(c.kh, c.k_st, c.tile_base(t), nullptr, c.N, kbuf(t), wave, lane);
+  }
+  __device__ inline void fetch_v(int t) const {
+    dma_rows<4, 64, true>(c.vh, c.v_st, c.tile_base(t), nullptr, c.N, vbuf(t), wave, lane);
+  }
+  __device__ inline void fresh(f32x16 (&s)[2][2], int t, int cls) {
+    if (cls == 2 || !has_ref)
+      special_tile<2>(s, st, c.tile_base(t), mp, cls == 2, !has_ref, c.c_log2, lane);
+    has_ref = true;
+  }
+  // one iteration: s_cur holds the logits of tile t (if cls_cur), s_nxt receives tile t+1
+  __device__ inline void iter(int t, f32x16 (&s_cur)[2][2], f32x16 (&s_nxt)[2][2]) {
+    if (t + 2 < c.T) fetch_k(t + 2);
+    if (t + 1 < c.T) fetch_v(t + 1);
+    const int cls_nxt = t + 1 < c.T ? classify_step<64>(c.tile_base(t + 1), mp) : 0;
+    bf16x8 p[2][2][2];
+    if (cls_cur != 0 && cls_nxt != 0) {
+      fused_qk_softmax(s_nxt, p, st, s_cur, lo, kbuf(t + 1), c.c_log2);
+    } else {
+      if (cls_nxt != 0) qk_tile<2>(s_nxt, st, lo, kbuf(t + 1));
+      if (cls_cur != 0) softmax_tile<2>(p, st, s_cur, c.c_log2);
+    }
+    if (cls_nxt != 0) fresh(s_nxt, t + 1, cls_nxt);
+    if (cls_cur != 0) pv_tile<2>(st, lo, vbuf(t), p);
+    cls_cur = cls_nxt;
+    MINF_WAIT_VMCNT(0);
+    __syncthreads();
+  }
+};
+
+__device__ inline void ashape_pass_pipelined(const AshapeCtx &c, WaveState &st, const LaneOfs &lo,
+                                             const MaskP &mp, int wave, int lane) {
+  AshapePipe pp{c, st, lo, mp, wave, lane, false, 0};
+  f32x16 sa[2][2], sb[2][2];
+  pp.fetch_k(0);
+  if (c.T > 1) pp.fetch_k(1);
+  pp.fetch_v(0);
+  MINF_WAIT_VMCNT(0);
+  __syncthreads();
+  pp.cls_cur = classify_step<64>(c.tile_base(0), mp);
+  if (pp.cls_cur != 0) {
+    qk_tile<2>(sa, st, lo, pp.kbuf(0));
+    pp.fresh(sa, 0, pp.cls_cur);
+  }
+  int t = 0;
+  for (; t + 1 < c.T; t += 2) {
+    pp.iter(t, sa, sb);
+    pp.iter(t + 1, sb, sa);
+  }
+  if (t < c.T) pp.iter(t, sa, sb);
+}
+
 __global__ __launch_bounds__(256) void ashape_kernel(QKV x, HeadList hl, int n_init, int n_local,
                                                      Sched sched) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -416,7 +645,7 @@ __global__ __launch_bounds__(256) void ashape_kernel(QKV x, HeadList hl, int n_i
   c.kh = x.k + kvh * x.k_sh; c.vh = x.v + kvh * x.v_sh; c.k_st = x.k_st; c.v_st = x.v_st;
   c.N = x.N; c.T1 = e1 / BK; c.T = c.T1 + (wq1 - s2) / BK; c.s2 = s2; c.lds = lds; c.c_log2 = x.c_log2;
 
-  ashape_pass<PASS_OPT>(c, st, lo, mp, wave, lane);
+  ashape_pass_pipelined(c, st, lo, mp, wave, lane);
   if (__syncthreads_or(needs_exact(st) ? 1 : 0)) {
     reset_for_max_pass(st);
     ashape_pass<PASS_MAX>(c, st, lo, mp, wave, lane);

@@ -37,15 +37,19 @@ __device__ inline int perm_row(int m) { return (m & ~12) | ((m & 4) << 1) | ((m 
 
 // ---------------------------------------------------------------------------
 // LDS tile layout.  A K or V tile is ROWS rows of 256 B, row-major, with the
-// 16-byte chunk c of row r stored at chunk position c ^ (r & 15).  The XOR
-// spreads the 16 rows that a group of 16 lanes reads at the same column over
-// all 64 banks.  The tile is filled by direct global -> LDS loads
+// 16-byte chunk c of row r stored at chunk position c ^ f(r & 15), where f swaps
+// the two 2-bit halves of its argument.  Any bijection f spreads the 16 rows
+// that 16 lanes read at one column (K operand, ds_read_b128) over all 64
+// banks; this one also sends 4 consecutive rows to 4 different 64-byte
+// quarters of the bank window, which the transposing V read needs (each half
+// wave touches 4 keys x 64 bytes).  The tile is filled by direct global -> LDS loads
 // (global_load_lds_dwordx4: lane L's 16 bytes land at base + 16 L, so one
 // instruction fills one 1 KiB block = 4 rows and every lane fetches the chunk
 // that belongs at its position); no VGPRs and no LDS store instructions are
 // spent on staging.
 // ---------------------------------------------------------------------------
-__device__ inline int swz_byte(int r, int c16) { return r * ROW_BYTES + ((c16 ^ (r & 15)) << 4); }
+__device__ inline int swz_f(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+__device__ inline int swz_byte(int r, int c16) { return r * ROW_BYTES + ((c16 ^ swz_f(r)) << 4); }
 
 // One direct global -> LDS load of 16 bytes per lane: lane L's bytes land at
 // LDS byte address lds_addr + 16 L (lds_addr wave-uniform).  Written as inline
@@ -91,7 +95,7 @@ __device__ inline void dma_rows(const bf16_t *g, int64_t stride, int kbase, cons
     for (int i = 0; i < ROWS / 4 / NW; ++i) {
       const int blk = wave + NW * i;
       const int r = 4 * blk + rl;
-      const int c = cpos ^ (r & 15);
+      const int c = cpos ^ swz_f(r);
       dma16_su(ubase, (unsigned)r * row_bytes + (unsigned)c * 16u, base + blk * 1024);
     }
     return;
@@ -100,7 +104,7 @@ __device__ inline void dma_rows(const bf16_t *g, int64_t stride, int kbase, cons
   for (int i = 0; i < ROWS / 4 / NW; ++i) {
     const int blk = wave + NW * i;
     const int r = 4 * blk + rl;
-    const int c = cpos ^ (r & 15);
+    const int c = cpos ^ swz_f(r);
     int key;
     if (CONTIG) {
       key = min(max(kbase + r, 0), N - 1);
