@@ -41,6 +41,8 @@
 
 namespace minf {
 
+constexpr int BS_LIST_CAP = 512;          // block ids staged in LDS per round of the Block-Sparse walk
+constexpr int VS_RUN_CAP = 256;           // slash runs staged in LDS per round of the Vertical-Slash walk
 constexpr int VCAP = 1024;               // compacted vertical columns held in LDS per round
 constexpr int TILE_BYTES = 64 * ROW_BYTES;   // 64 rows of K or of V
 constexpr int HALF_BYTES = 32 * ROW_BYTES;   // 32 rows
@@ -360,58 +362,56 @@ __device__ inline void pv_tile(WaveState &st, const LaneOfs &lo, const char *tV,
       }
 }
 
-// QK of one 64-key tile fused with the softmax of the previous tile, interleaved
-// by hand: 8 rounds of {4 MFMAs of k-step ks; one eighth of the exp work; LDS
-// reads of k-step ks+1}.  The vector ALU work of a round (about 30 instructions)
-// runs in the shadow of the round's 4 MFMAs (128 cycles).  sched_barrier(0)
-// keeps the compiler from regrouping the rounds.
-__device__ inline void fused_qk_softmax(f32x16 (&s_nxt)[2][2], bf16x8 (&p)[2][2][2], WaveState &st,
-                                        const f32x16 (&s_cur)[2][2], const LaneOfs &lo, const char *tK,
+// QK of one step fused with the softmax of the previous step, interleaved by
+// hand: 8 rounds of {the 2 MB MFMAs of k-step ks; one eighth of the exp work;
+// LDS reads of k-step ks+1}.  The vector ALU work of a round runs in the shadow
+// of the round's MFMAs (32 cycles each).  sched_barrier(0) keeps the compiler
+// from regrouping the rounds.
+template <int MB>
+__device__ inline void fused_qk_softmax(f32x16 (&s_nxt)[MB][2], bf16x8 (&p)[2][MB][2], WaveState &st,
+                                        const f32x16 (&s_cur)[MB][2], const LaneOfs &lo, const char *tK,
                                         float c_log2) {
+  constexpr int EPR = 4 * MB;            // logits per lane handled per round
   const float m0 = st.m[0], m1 = st.m[1];
   float lsum0 = 0.f, lsum1 = 0.f;
-  bf16x8 a0 = lds_read_k(tK, lo.k[0]), a1 = lds_read_k(tK, lo.k[0] + HALF_BYTES);
+  bf16x8 a[MB];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) a[mb] = lds_read_k(tK, lo.k[0] + mb * HALF_BYTES);
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) {
-    const bf16x8 c0 = a0, c1 = a1;
-    if (ks + 1 < 8) {
-      a0 = lds_read_k(tK, lo.k[ks + 1]);
-      a1 = lds_read_k(tK, lo.k[ks + 1] + HALF_BYTES);
-    }
-    if (ks == 0) {
-      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      s_nxt[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c0, st.q[0][0], zero, 0, 0, 0);
-      s_nxt[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c0, st.q[1][0], zero, 0, 0, 0);
-      s_nxt[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c1, st.q[0][0], zero, 0, 0, 0);
-      s_nxt[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c1, st.q[1][0], zero, 0, 0, 0);
-    } else {
-      s_nxt[0][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c0, st.q[0][ks], s_nxt[0][0], 0, 0, 0);
-      s_nxt[0][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c0, st.q[1][ks], s_nxt[0][1], 0, 0, 0);
-      s_nxt[1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c1, st.q[0][ks], s_nxt[1][0], 0, 0, 0);
-      s_nxt[1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c1, st.q[1][ks], s_nxt[1][1], 0, 0, 0);
-    }
-    // softmax slice ks of the previous tile: (nb, mb, t) = (ks / 4, (ks / 2) % 2, ks % 2)
-    const int nb = ks >> 2, mb = (ks >> 1) & 1, t = ks & 1;
-    const float m_use = nb == 0 ? m0 : m1;
-    float e[8];
-    float part = 0.f;
+    bf16x8 c[MB];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      e[i] = fast_exp2(fmaf(s_cur[mb][nb][8 * t + i], c_log2, -m_use));
-      part += e[i];
+    for (int mb = 0; mb < MB; ++mb) {
+      c[mb] = a[mb];
+      if (ks + 1 < 8) a[mb] = lds_read_k(tK, lo.k[ks + 1] + mb * HALF_BYTES);
     }
-    if (nb == 0) lsum0 += part; else lsum1 += part;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+      if (ks == 0) {
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        s_nxt[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[mb], st.q[0][0], zero, 0, 0, 0);
+        s_nxt[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[mb], st.q[1][0], zero, 0, 0, 0);
+      } else {
+        s_nxt[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[mb], st.q[0][ks], s_nxt[mb][0], 0, 0, 0);
+        s_nxt[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(c[mb], st.q[1][ks], s_nxt[mb][1], 0, 0, 0);
+      }
+    }
+    // softmax slice ks of the previous step; logits are walked in the order [nb][mb][r]
+#pragma unroll
+    for (int i = 0; i < EPR; i += 2) {
+      const int e = ks * EPR + i;
+      const int nb = e / (16 * MB), mb = (e % (16 * MB)) / 16, r = e % 16;
+      const float m_use = nb == 0 ? m0 : m1;
+      const float e0 = fast_exp2(fmaf(s_cur[mb][nb][r], c_log2, -m_use));
+      const float e1 = fast_exp2(fmaf(s_cur[mb][nb][r + 1], c_log2, -m_use));
+      if (nb == 0) lsum0 += e0 + e1; else lsum1 += e0 + e1;
+      const f32x2 two = {e0, e1};
+      const bf16x2 b2 = __builtin_convertvector(two, bf16x2);
+      p[nb][mb][r >> 3][r & 7] = b2[0];
+      p[nb][mb][r >> 3][(r & 7) + 1] = b2[1];
+    }
     // keep this round's adds in this round (they would otherwise sink to the end of the block)
     asm volatile("" : "+v"(lsum0), "+v"(lsum1));
-    bf16x8 pk;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const f32x2 two = {e[2 * i], e[2 * i + 1]};
-      const bf16x2 b2 = __builtin_convertvector(two, bf16x2);
-      pk[2 * i] = b2[0];
-      pk[2 * i + 1] = b2[1];
-    }
-    p[nb][mb][t] = pk;
     __builtin_amdgcn_sched_barrier(0);
   }
   st.l[0] += lsum0;
@@ -576,7 +576,7 @@ struct AshapePipe {
     const int cls_nxt = t + 1 < c.T ? classify_step<64>(c.tile_base(t + 1), mp) : 0;
     bf16x8 p[2][2][2];
     if (cls_cur != 0 && cls_nxt != 0) {
-      fused_qk_softmax(s_nxt, p, st, s_cur, lo, kbuf(t + 1), c.c_log2);
+      fused_qk_softmax<2>(s_nxt, p, st, s_cur, lo, kbuf(t + 1), c.c_log2);
     } else {
       if (cls_nxt != 0) qk_tile<2>(s_nxt, st, lo, kbuf(t + 1));
       if (cls_cur != 0) softmax_tile<2>(p, st, s_cur, c.c_log2);
@@ -674,6 +674,115 @@ __device__ inline void fetch_step(const StepBuf &sb, int s, const bf16_t *kh, co
   dma_rows<1, 32, CONTIG>(vh, v_st, kbase, cols, N, sb.v(s), 0, lane);
 }
 
+// Rare path on fresh logits of a gathered step: attended iff key <= query row.
+__device__ inline void special_gather(f32x16 (&s)[1][2], WaveState &st, const int *cols, const MaskP &mp,
+                                      bool first, float c_log2, int lane) {
+  const int n = lane & 31, h = lane >> 5;
+  int keys[16];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int4 a = *reinterpret_cast<const int4 *>(cols + 16 * t + 8 * h);
+    const int4 b = *reinterpret_cast<const int4 *>(cols + 16 * t + 8 * h + 4);
+    keys[8 * t + 0] = a.x; keys[8 * t + 1] = a.y; keys[8 * t + 2] = a.z; keys[8 * t + 3] = a.w;
+    keys[8 * t + 4] = b.x; keys[8 * t + 5] = b.y; keys[8 * t + 6] = b.z; keys[8 * t + 7] = b.w;
+  }
+#pragma unroll
+  for (int r = 0; r < 16; ++r)
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) s[0][nb][r] = keys[r] <= mp.q0 + 32 * nb + n ? s[0][nb][r] : -INFINITY;
+  if (first) {
+    MaskP none = mp;
+    special_tile<1>(s, st, 0, none, false, true, c_log2, lane);
+  }
+}
+
+// One 32-key step of a single-wave kernel.  cols == nullptr: keys kbase .. kbase+31
+// with the mask window [lo, hi); else keys cols[0..31] (LDS).  cls 1: no element is
+// masked, 2: the element mask must be applied.
+struct Step {
+  int kbase, lo, hi, cls;
+  const int *cols;
+};
+
+// Software-pipelined optimistic pass over the steps a generator yields (skipped
+// steps are never yielded).  At the top of iteration t the loads of K(t+2) and
+// V(t+1) are issued; then QK(t+1) runs fused with the softmax of step t, then
+// P V of step t.  K(t+2) lands in the buffer QK(t) has finished with.
+template <class Gen, bool GATHER>
+struct WavePipe {
+  Gen &gen;
+  WaveState &st;
+  bool &has_ref;
+  const LaneOfs &lo;
+  StepBuf buf;
+  const bf16_t *kh, *vh;
+  int64_t k_st, v_st;
+  int N;
+  MaskP mp;
+  float c_log2;
+  int lane;
+  Step d0, d1, d2;
+  bool h0, h1, h2;
+
+  __device__ inline void fetch_k(const Step &d, int slot) const {
+    if (GATHER) dma_rows<1, 32, false>(kh, k_st, 0, d.cols, N, buf.k(slot), 0, lane);
+    else dma_rows<1, 32, true>(kh, k_st, d.kbase, nullptr, N, buf.k(slot), 0, lane);
+  }
+  __device__ inline void fetch_v(const Step &d, int slot) const {
+    if (GATHER) dma_rows<1, 32, false>(vh, v_st, 0, d.cols, N, buf.v(slot), 0, lane);
+    else dma_rows<1, 32, true>(vh, v_st, d.kbase, nullptr, N, buf.v(slot), 0, lane);
+  }
+  __device__ inline void fresh(f32x16 (&s)[1][2], const Step &d) {
+    if (d.cls == 2 || !has_ref) {
+      if (GATHER) {
+        special_gather(s, st, d.cols, mp, !has_ref, c_log2, lane);
+      } else {
+        MaskP m = mp;
+        m.lo = d.lo; m.hi = d.hi;
+        special_tile<1>(s, st, d.kbase, m, d.cls == 2, !has_ref, c_log2, lane);
+      }
+    }
+    has_ref = true;
+  }
+  __device__ inline void iter(int t, f32x16 (&s_cur)[1][2], f32x16 (&s_nxt)[1][2]) {
+    int issued = 0;
+    if (h2) { fetch_k(d2, t & 1); issued += 8; }
+    if (h1) { fetch_v(d1, (t + 1) & 1); issued += 8; }
+    if (issued == 16) MINF_WAIT_VMCNT(16); else MINF_WAIT_VMCNT(0);
+    bf16x8 p[2][1][2];
+    if (h1) {
+      fused_qk_softmax<1>(s_nxt, p, st, s_cur, lo, buf.k((t + 1) & 1), c_log2);
+      fresh(s_nxt, d1);
+    } else {
+      softmax_tile<1>(p, st, s_cur, c_log2);
+    }
+    pv_tile<1>(st, lo, buf.v(t & 1), p);
+    d0 = d1; d1 = d2;
+    h0 = h1; h1 = h2;
+    h2 = h2 && gen.next(d2);
+  }
+  __device__ inline void run() {
+    h0 = gen.next(d0);
+    h1 = h0 && gen.next(d1);
+    h2 = h1 && gen.next(d2);
+    if (!h0) return;
+    fetch_k(d0, 0);
+    if (h1) fetch_k(d1, 1);
+    fetch_v(d0, 0);
+    MINF_WAIT_VMCNT(0);
+    f32x16 sa[1][2], sb[1][2];
+    qk_tile<1>(sa, st, lo, buf.k(0));
+    fresh(sa, d0);
+    int t = 0;
+    while (h0) {
+      iter(t, sa, sb);
+      if (!h0) break;
+      iter(t + 1, sb, sa);
+      t += 2;
+    }
+  }
+};
+
 // ---------------------------------------------------------------------------
 // Block-Sparse: one wave per (head, query block); steps = halves of the listed
 // key blocks.
@@ -717,6 +826,32 @@ __device__ inline void bs_pass(const BsCtx &c, WaveState &st, const LaneOfs &lo,
   }
 }
 
+// Generator of the Block-Sparse steps: both halves of every listed block that
+// holds a key some row may attend (ids outside [0, NB) and blocks past the
+// diagonal are dropped).
+struct BsGen {
+  const BsCtx &c;
+  const MaskP &mp;
+  int i, half;
+  __device__ inline bool next(Step &d) {
+    while (i < c.cnt) {
+      const int b = c.list[i];
+      if (b >= 0 && b < c.NB) {
+        const int kbase = b * BK + 32 * half;
+        const int cls = classify_step<32>(kbase, mp);
+        if (half == 1) { ++i; half = 0; } else half = 1;
+        if (cls != 0) {
+          d.kbase = kbase; d.lo = mp.lo; d.hi = mp.hi; d.cls = cls; d.cols = nullptr;
+          return true;
+        }
+      } else {
+        ++i; half = 0;
+      }
+    }
+    return false;
+  }
+};
+
 __global__ __launch_bounds__(64) void bs_kernel(QKV x, HeadList hl, const int32_t *blk_idx,
                                                 const int32_t *blk_cnt, int topk, Sched sched) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -740,11 +875,27 @@ __global__ __launch_bounds__(64) void bs_kernel(QKV x, HeadList hl, const int32_
   BsCtx c;
   c.kh = x.k + kvh * x.k_sh; c.vh = x.v + kvh * x.v_sh; c.k_st = x.k_st; c.v_st = x.v_st;
   c.N = x.N; c.NB = NB; c.buf = StepBuf{lds}; c.c_log2 = x.c_log2;
-  c.list = blk_idx + ((int64_t)slot * NB + b) * topk;
+  // the block list of this query block is staged in LDS (at most BS_LIST_CAP ids per
+  // round of the walk) so that the step generator never waits on global memory
+  const int32_t *glist = blk_idx + ((int64_t)slot * NB + b) * topk;
   c.cnt = min(max(blk_cnt[(int64_t)slot * NB + b], 0), topk);
+  int *llist = reinterpret_cast<int *>(lds + 4 * HALF_BYTES);
+  c.list = llist;
 
-  bs_pass<PASS_OPT>(c, st, lo, mp, lane);
+  const int total = c.cnt;
+  bool has_ref = false;
+  for (int r0 = 0; r0 < total; r0 += BS_LIST_CAP) {
+    c.cnt = min(total - r0, BS_LIST_CAP);
+    for (int i = lane; i < c.cnt; i += 64) llist[i] = glist[r0 + i];
+    __syncthreads();
+    BsGen gen{c, mp, 0, 0};
+    WavePipe<BsGen, false> pipe{gen, st, has_ref, lo, c.buf, c.kh, c.vh, c.k_st, c.v_st, c.N, mp, c.c_log2, lane};
+    pipe.run();
+    __syncthreads();
+  }
   if (needs_exact(st)) {
+    c.list = glist;
+    c.cnt = total;
     reset_for_max_pass(st);
     bs_pass<PASS_MAX>(c, st, lo, mp, lane);
     finish_max_pass(st, x.c_log2);
@@ -854,6 +1005,102 @@ __device__ inline void vs_pass(const VsCtx &c, WaveState &st, const LaneOfs &lo,
   }
 }
 
+// Generators of the Vertical-Slash steps for the pipelined pass.
+// Slash runs: a chunk of runs staged in LDS, each walked 32 keys at a time.
+struct VsRunGen {
+  const int2 *runs;     // LDS
+  int n, q0, N;
+  int iv, ks, ke, pos;
+  __device__ inline bool next(Step &d) {
+    while (true) {
+      if (pos < ke) {
+        d.kbase = pos; d.lo = ks; d.hi = ke; d.cols = nullptr;
+        // the run is causal up to q0 + 63 by construction; only the key window and
+        // the diagonal can mask elements
+        d.cls = (pos >= ks && pos + 31 < ke && pos + 31 <= q0) ? 1 : 2;
+        pos += 32;
+        return true;
+      }
+      if (iv >= n) return false;
+      const int2 r = runs[iv];
+      ++iv;
+      ks = max(q0 - r.y + 1, 0);
+      ke = min(q0 - r.x + 1, N);
+      pos = ks;
+    }
+  }
+};
+
+// Gathered verticals: steps of 32 entries of the compacted column list (LDS).
+struct VsColGen {
+  const int *cols;
+  int nstep, q0, t;
+  __device__ inline bool next(Step &d) {
+    if (t >= nstep) return false;
+    d.kbase = 0; d.lo = 0; d.hi = 0;
+    d.cols = cols + 32 * t;
+    d.cls = d.cols[31] <= q0 ? 1 : 2;     // ascending list: the last entry decides (KEY_NONE pads)
+    ++t;
+    return true;
+  }
+};
+
+// Optimistic pass of the Vertical-Slash kernel, software pipelined.
+__device__ inline void vs_pass_pipelined(const VsCtx &c, WaveState &st, const LaneOfs &lo, const MaskP &mp,
+                                         int2 *lruns, int lane) {
+  const int q0 = c.q0;
+  bool has_ref = false;
+  // ---- phase A: slash runs, staged VS_RUN_CAP at a time
+  for (int r0 = 0; r0 < c.n_c; r0 += VS_RUN_CAP) {
+    const int n = min(c.n_c - r0, VS_RUN_CAP);
+    if (c.runs[r0].x > q0) break;             // runs ascend: no later run reaches a key >= 0
+    int usable = 0;
+    for (int i = lane; i < n; i += 64) {
+      const int2 r = c.runs[r0 + i];
+      lruns[i] = r;
+      usable += r.x <= q0 ? 1 : 0;
+    }
+    // number of runs of the chunk that reach a key >= 0 (they form a prefix)
+    for (int off = 32; off > 0; off >>= 1) usable += __shfl_xor(usable, off);
+    __syncthreads();
+    VsRunGen gen{lruns, usable, q0, c.N, 0, 0, 0, 0};
+    WavePipe<VsRunGen, false> pipe{gen, st, has_ref, lo, c.buf, c.kh, c.vh, c.k_st, c.v_st, c.N, mp, c.c_log2, lane};
+    pipe.run();
+    __syncthreads();
+    if (usable < n) break;
+  }
+  // ---- phase B: verticals
+  const int qlast = q0 + BQ - 1;
+  int *cols = c.cols;
+  int vpos = 0;
+  while (vpos < c.n_v) {
+    int ncol = 0;
+    while (vpos < c.n_v && ncol <= VCAP - 64) {
+      const int i = vpos + lane;
+      const int v = i < c.n_v ? c.vlist[i] : KEY_NONE;
+      bool ok = v <= qlast && v >= 0;
+      if (ok) {
+        const int t = q0 - v + 64;     // bit index of offset q0 - v, in [1, q0 + 64]
+        ok = ((c.bits[t >> 5] >> (t & 31)) & 1u) == 0u;
+      }
+      const unsigned long long bal = __builtin_amdgcn_ballot_w64(ok);
+      const int before = __builtin_popcountll(bal & ((1ull << lane) - 1ull));
+      if (ok) cols[ncol + before] = v;
+      ncol += __builtin_popcountll(bal);
+      vpos += 64;
+      if (__shfl(v, 0) > qlast) { vpos = c.n_v; break; }
+    }
+    if (ncol == 0) continue;
+    const int nstep = (ncol + 31) / 32;
+    if (lane + ncol < nstep * 32) cols[ncol + lane] = KEY_NONE;   // pad the last step
+    __syncthreads();
+    VsColGen gen{cols, nstep, q0, 0};
+    WavePipe<VsColGen, true> pipe{gen, st, has_ref, lo, c.buf, c.kh, c.vh, c.k_st, c.v_st, c.N, mp, c.c_log2, lane};
+    pipe.run();
+    __syncthreads();
+  }
+}
+
 __global__ __launch_bounds__(64) void vs_kernel(QKV x, HeadList hl, const int32_t *v_idx,
                                                 const int32_t *cover, const uint32_t *cover_bits,
                                                 const int32_t *counts, int nv, int ns, int cover_words,
@@ -887,7 +1134,7 @@ __global__ __launch_bounds__(64) void vs_kernel(QKV x, HeadList hl, const int32_
   MaskP mp;
   mp.q0 = q0; mp.n_init = KEY_NONE; mp.n_local = 1; mp.lo = 0; mp.hi = 0;
 
-  vs_pass<PASS_OPT>(c, st, lo, mp, lane);
+  vs_pass_pipelined(c, st, lo, mp, reinterpret_cast<int2 *>(c.cols + VCAP + 64), lane);
   if (needs_exact(st)) {
     reset_for_max_pass(st);
     vs_pass<PASS_MAX>(c, st, lo, mp, lane);
@@ -918,7 +1165,7 @@ hipError_t launch_bs(const QKV &x, const HeadList &hl, const int32_t *blk_idx, c
                      int topk, hipStream_t st) {
   const int NB = x.N / BQ;
   const Sched s = make_sched((int64_t)hl.n * NB);
-  const size_t lds = 4 * HALF_BYTES;
+  const size_t lds = 4 * HALF_BYTES + BS_LIST_CAP * sizeof(int);
   hipError_t e = set_lds(reinterpret_cast<const void *>(bs_kernel), lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(bs_kernel, dim3(s.per_xcd * 8), dim3(64), lds, st, x, hl, blk_idx, blk_cnt, topk, s);
@@ -930,7 +1177,7 @@ hipError_t launch_vs(const QKV &x, const HeadList &hl, const int32_t *v_idx, con
                      int cover_words, hipStream_t st) {
   const int NB = x.N / BQ;
   const Sched s = make_sched((int64_t)hl.n * NB);
-  const size_t lds = 4 * HALF_BYTES + (VCAP + 64) * sizeof(int);
+  const size_t lds = 4 * HALF_BYTES + (VCAP + 64) * sizeof(int) + VS_RUN_CAP * sizeof(int2);
   hipError_t e = set_lds(reinterpret_cast<const void *>(vs_kernel), lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(vs_kernel, dim3(s.per_xcd * 8), dim3(64), lds, st, x, hl, v_idx, cover, cover_bits,
