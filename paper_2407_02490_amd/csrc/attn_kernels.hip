@@ -316,6 +316,26 @@ __device__ inline void special_tile(f32x16 (&s)[MB][2], WaveState &st, int kbase
   }
 }
 
+// Cheap element mask for steps whose only constraints are a key window and
+// causality (Block-Sparse, Vertical-Slash, dense): attended iff
+// lo <= key < min(hi, query row + 1), one unsigned compare per element.
+template <int MB>
+__device__ inline void window_mask(f32x16 (&s)[MB][2], int kbase, const MaskP &mp, int lane) {
+  const int n = lane & 31, h = lane >> 5;
+  const int rel = kbase + 8 * h - mp.lo;                       // key - lo for index 0 of this lane
+  unsigned span[2];
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) span[nb] = (unsigned)max(min(mp.hi, mp.q0 + 32 * nb + n + 1) - mp.lo, 0);
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const unsigned d = (unsigned)(rel + 32 * mb + 16 * (r >> 3) + (r & 7));
+#pragma unroll
+      for (int nb = 0; nb < 2; ++nb) s[mb][nb][r] = d < span[nb] ? s[mb][nb][r] : -INFINITY;
+    }
+}
+
 template <int MB>
 __device__ inline void softmax_tile(bf16x8 (&p)[2][MB][2], WaveState &st, const f32x16 (&s)[MB][2],
                                     float c_log2) {
@@ -485,28 +505,6 @@ __device__ inline void finish_max_pass(WaveState &st, float c_log2) {
   }
 }
 
-// Work-item decode shared by the kernels: heads are taken in chunks of 4
-// list slots, and inside a chunk the block index varies slowest (descending,
-// heaviest first), so that the workgroups resident on one XCD at a time are a
-// few neighbouring query blocks of up to 4 heads (one GQA group when the head
-// list is sorted) and share their K/V tiles in that XCD's L2.
-__device__ inline void decode_item(int logical, int n_heads, int n_blk, int &slot, int &blk) {
-  const int n_full = n_heads >> 2, rem = n_heads & 3;
-  const int full_items = n_full * 4 * n_blk;
-  int r;
-  if (logical < full_items) {
-    const int chunk = logical / (4 * n_blk);
-    r = logical - chunk * 4 * n_blk;
-    slot = chunk * 4 + (r & 3);
-    r >>= 2;
-  } else {
-    r = logical - full_items;
-    slot = n_full * 4 + r % rem;
-    r = r / rem;
-  }
-  blk = n_blk - 1 - r;
-}
-
 // ---------------------------------------------------------------------------
 // A-shape (and dense causal: n_init = 0, n_local >= N).  4 waves, 256 query
 // rows of one head per workgroup; shared, double-buffered 64-key K/V tiles.
@@ -614,11 +612,9 @@ __device__ inline void ashape_pass_pipelined(const AshapeCtx &c, WaveState &st, 
 __global__ __launch_bounds__(256) void ashape_kernel(QKV x, HeadList hl, int n_init, int n_local,
                                                      Sched sched) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  const int logical = logical_wg(sched);
-  if (logical < 0) return;
-  const int NB = x.N / BQ, NSB = (NB + 3) / 4;
+  const int NB = x.N / BQ;
   int slot, sb;
-  decode_item(logical, hl.n, NSB, slot, sb);
+  if (!decode_wg(sched, slot, sb)) return;
   const int head = hl.h[slot], kvh = head / x.group;
   const bf16_t *qh = x.q + head * x.q_sh;
   bf16_t *oh = x.o + head * x.o_sh;
@@ -739,7 +735,8 @@ struct WavePipe {
       } else {
         MaskP m = mp;
         m.lo = d.lo; m.hi = d.hi;
-        special_tile<1>(s, st, d.kbase, m, d.cls == 2, !has_ref, c_log2, lane);
+        if (d.cls == 2) window_mask<1>(s, d.kbase, m, lane);
+        if (!has_ref) special_tile<1>(s, st, d.kbase, m, false, true, c_log2, lane);
       }
     }
     has_ref = true;
@@ -855,11 +852,9 @@ struct BsGen {
 __global__ __launch_bounds__(64) void bs_kernel(QKV x, HeadList hl, const int32_t *blk_idx,
                                                 const int32_t *blk_cnt, int topk, Sched sched) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  const int logical = logical_wg(sched);
-  if (logical < 0) return;
   const int NB = x.N / BQ;
   int slot, b;
-  decode_item(logical, hl.n, NB, slot, b);
+  if (!decode_wg(sched, slot, b)) return;
   const int head = hl.h[slot], kvh = head / x.group;
   const bf16_t *qh = x.q + head * x.q_sh;
   bf16_t *oh = x.o + head * x.o_sh;
@@ -1106,11 +1101,9 @@ __global__ __launch_bounds__(64) void vs_kernel(QKV x, HeadList hl, const int32_
                                                 const int32_t *counts, int nv, int ns, int cover_words,
                                                 Sched sched) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  const int logical = logical_wg(sched);
-  if (logical < 0) return;
   const int NB = x.N / BQ;
   int slot, b;
-  decode_item(logical, hl.n, NB, slot, b);
+  if (!decode_wg(sched, slot, b)) return;
   const int head = hl.h[slot], kvh = head / x.group;
   const bf16_t *qh = x.q + head * x.q_sh;
   bf16_t *oh = x.o + head * x.o_sh;
@@ -1153,7 +1146,7 @@ static hipError_t set_lds(const void *fn, size_t bytes) {
 
 hipError_t launch_ashape(const QKV &x, const HeadList &hl, int n_init, int n_local, hipStream_t st) {
   const int NB = x.N / BQ, NSB = (NB + 3) / 4;
-  const Sched s = make_sched((int64_t)hl.n * NSB);
+  const Sched s = make_sched(hl.n, NSB);
   const size_t lds = 4 * TILE_BYTES;
   hipError_t e = set_lds(reinterpret_cast<const void *>(ashape_kernel), lds);
   if (e != hipSuccess) return e;
@@ -1164,7 +1157,7 @@ hipError_t launch_ashape(const QKV &x, const HeadList &hl, int n_init, int n_loc
 hipError_t launch_bs(const QKV &x, const HeadList &hl, const int32_t *blk_idx, const int32_t *blk_cnt,
                      int topk, hipStream_t st) {
   const int NB = x.N / BQ;
-  const Sched s = make_sched((int64_t)hl.n * NB);
+  const Sched s = make_sched(hl.n, NB);
   const size_t lds = 4 * HALF_BYTES + BS_LIST_CAP * sizeof(int);
   hipError_t e = set_lds(reinterpret_cast<const void *>(bs_kernel), lds);
   if (e != hipSuccess) return e;
@@ -1176,7 +1169,7 @@ hipError_t launch_vs(const QKV &x, const HeadList &hl, const int32_t *v_idx, con
                      const uint32_t *cover_bits, const int32_t *counts, int nv, int ns,
                      int cover_words, hipStream_t st) {
   const int NB = x.N / BQ;
-  const Sched s = make_sched((int64_t)hl.n * NB);
+  const Sched s = make_sched(hl.n, NB);
   const size_t lds = 4 * HALF_BYTES + (VCAP + 64) * sizeof(int) + VS_RUN_CAP * sizeof(int2);
   hipError_t e = set_lds(reinterpret_cast<const void *>(vs_kernel), lds);
   if (e != hipSuccess) return e;

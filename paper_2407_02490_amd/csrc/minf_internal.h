@@ -29,23 +29,60 @@ struct HeadList {
   int32_t h[MINF_MAX_HEADS];
 };
 
-// Mapping of hardware workgroup ids to logical work items.  Consecutive
-// hardware ids land on different XCDs (8 of them, each with its own L2), so a
-// logical id is formed as (id % 8) * per_xcd + id / 8: every XCD then walks a
-// contiguous range of logical items and neighbours share K/V in its L2.
+// Mapping of hardware workgroup ids to work items (head slot, block).
+// Consecutive hardware ids land on different XCDs (8 of them, each with its own
+// 4 MB L2), and workgroups are handed to the XCDs in order, so an XCD whose
+// workgroups run longer than the others' starves the rest of the chip
+// (measured: per-XCD head ranges cost 44% idle time on heads of unequal
+// weight).  Therefore every XCD gets the same mix at every moment: heads are
+// taken in chunks of 4 list slots; inside a chunk the blocks, heaviest (last)
+// first, are cut into stripes of `stripe` consecutive blocks that are dealt
+// to the XCDs in serpentine order; inside a stripe the order is (block, head).  The
+// workgroups resident on one XCD at a time are then a few neighbouring blocks of
+// up to 4 heads (one GQA group when the head list is sorted) and share their K/V
+// tiles in that XCD's L2, while all XCDs work on the same heads at once.
 struct Sched {
-  int32_t total, per_xcd;
+  int32_t n_heads, n_blk, stripe, ls;   // ls = stripes per XCD per chunk
+  int32_t per_xcd;                      // workgroups per XCD (grid = 8 * per_xcd)
 };
-inline Sched make_sched(int64_t total) {
+inline Sched make_sched(int n_heads, int n_blk) {
   Sched s;
-  s.total = (int32_t)total;
-  s.per_xcd = (int32_t)((total + 7) / 8);
+  s.n_heads = n_heads;
+  s.n_blk = n_blk;
+  int stripe = n_blk / 64;
+  s.stripe = stripe < 1 ? 1 : (stripe > 32 ? 32 : stripe);
+  const int n_stripes = (n_blk + s.stripe - 1) / s.stripe;
+  s.ls = (n_stripes + 7) / 8;
+  s.per_xcd = s.ls * s.stripe * n_heads;   // sum over chunks of ls * stripe * chunk size
   return s;
 }
-__device__ inline int logical_wg(const Sched &s) {
-  int hw = blockIdx.x;
-  int l = (hw & 7) * s.per_xcd + (hw >> 3);
-  return l < s.total ? l : -1;
+// Returns false if this workgroup has no work item.
+__device__ inline bool decode_wg(const Sched &s, int &slot, int &blk) {
+  const int hw = blockIdx.x;
+  const int xcd = hw & 7;
+  int seq = hw >> 3;
+  const int per_full = s.ls * s.stripe * 4;            // items per XCD of a full chunk
+  const int n_full = s.n_heads >> 2;
+  int chunk, csize;
+  if (seq < n_full * per_full) {
+    chunk = seq / per_full;
+    seq -= chunk * per_full;
+    csize = 4;
+  } else {
+    chunk = n_full;
+    seq -= n_full * per_full;
+    csize = s.n_heads & 3;
+  }
+  const int per_stripe = s.stripe * csize;
+  const int lstripe = seq / per_stripe;
+  const int r = seq - lstripe * per_stripe;
+  // stripes are dealt to the XCDs in serpentine order (0..7, 7..0, ...) so that work that
+  // grows with the block index (dense causal) stays balanced across XCDs
+  const int pos = (lstripe & 1) ? 7 - xcd : xcd;
+  const int rank = (lstripe * 8 + pos) * s.stripe + r / csize;   // 0 = last block
+  slot = chunk * 4 + r % csize;
+  blk = s.n_blk - 1 - rank;
+  return rank < s.n_blk;
 }
 
 // attention launches (attn_kernels.hip)
