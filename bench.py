@@ -248,6 +248,9 @@ def main():
     ap.add_argument("--no-128k", action="store_true", help="skip the three 128K single-pattern layers")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense causal baseline")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device-to-device copy (known HBM bytes) so that "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE readings can be scaled")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (heads would shard across "
@@ -255,6 +258,15 @@ def main():
         sys.exit(2)
     B.lib()
     torch.cuda.set_device(0)
+    if a.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 2.0, out=dst)          # a plain streaming kernel: reads 2^30 B, writes 2^30 B
+        torch.cuda.synchronize()
+        log("copy calibration: 3 x (1 GiB read + 1 GiB write) elementwise launches done")
+        del src, dst
+        torch.cuda.empty_cache()
 
     extra = {}
     # ---- 128K single-pattern layers first (smaller; freed before the 1M layer)
