@@ -367,19 +367,29 @@ __device__ inline void softmax_tile(bf16x8 (&p)[2][MB][2], WaveState &st, const 
   }
 }
 
+// O^T += V^T P^T for one step.  The V^T operands are fetched from LDS two
+// MFMA pairs ahead of their use (each pair runs 64 cycles, an LDS read takes
+// longer than that to return).
 template <int MB>
 __device__ inline void pv_tile(WaveState &st, const LaneOfs &lo, const char *tV, const bf16x8 (&p)[2][MB][2]) {
+  constexpr int NSTEP = MB * 2 * 4;      // (mb, t, db)
+  constexpr int AHEAD = 2;
+  bf16x8 a[NSTEP];
+  auto fetch = [&](int i) {
+    const int mb = i / 8, t = (i / 4) & 1, db = i & 3;
+    const int base = (32 * mb + 16 * t) * ROW_BYTES;
+    return lds_read_vt(tV, lo.v[db][0] + base, lo.v[db][1] + base);
+  };
 #pragma unroll
-  for (int mb = 0; mb < MB; ++mb)
+  for (int i = 0; i < AHEAD; ++i) a[i] = fetch(i);
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
-#pragma unroll
-      for (int db = 0; db < 4; ++db) {
-        const int base = (32 * mb + 16 * t) * ROW_BYTES;
-        const bf16x8 a = lds_read_vt(tV, lo.v[db][0] + base, lo.v[db][1] + base);
-        st.o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p[0][mb][t], st.o[db][0], 0, 0, 0);
-        st.o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, p[1][mb][t], st.o[db][1], 0, 0, 0);
-      }
+  for (int i = 0; i < NSTEP; ++i) {
+    if (i + AHEAD < NSTEP) a[i + AHEAD] = fetch(i + AHEAD);
+    const int mb = i / 8, t = (i / 4) & 1, db = i & 3;
+    st.o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], p[0][mb][t], st.o[db][0], 0, 0, 0);
+    st.o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], p[1][mb][t], st.o[db][1], 0, 0, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  }
 }
 
 // QK of one step fused with the softmax of the previous step, interleaved by
@@ -513,6 +523,7 @@ __device__ inline void finish_max_pass(WaveState &st, float c_log2) {
 struct AshapeCtx {
   const bf16_t *kh, *vh;
   int64_t k_st, v_st;
+  DmaLane dk, dv;
   int N, T1, T, s2;
   char *lds;
   float c_log2;
@@ -524,8 +535,8 @@ __device__ inline void ashape_pass(const AshapeCtx &c, WaveState &st, const Lane
                                    int wave, int lane) {
   auto fetch = [&](int t) {
     char *stg = c.lds + (t & 1) * 2 * TILE_BYTES;
-    dma_rows<4, 64, true>(c.kh, c.k_st, c.tile_base(t), nullptr, c.N, stg, wave, lane);
-    dma_rows<4, 64, true>(c.vh, c.v_st, c.tile_base(t), nullptr, c.N, stg + TILE_BYTES, wave, lane);
+    dma_rows<4, 64, true>(c.kh, c.k_st, c.dk, c.tile_base(t), nullptr, c.N, stg, wave, lane);
+    dma_rows<4, 64, true>(c.vh, c.v_st, c.dv, c.tile_base(t), nullptr, c.N, stg + TILE_BYTES, wave, lane);
   };
   bool has_ref = false;
   fetch(0);
@@ -557,10 +568,10 @@ struct AshapePipe {
   __device__ inline char *kbuf(int t) const { return c.lds + (t & 1) * TILE_BYTES; }
   __device__ inline char *vbuf(int t) const { return c.lds + (2 + (t & 1)) * TILE_BYTES; }
   __device__ inline void fetch_k(int t) const {
-    dma_rows<4, 64, true>(c.kh, c.k_st, c.tile_base(t), nullptr, c.N, kbuf(t), wave, lane);
+    dma_rows<4, 64, true>(c.kh, c.k_st, c.dk, c.tile_base(t), nullptr, c.N, kbuf(t), wave, lane);
   }
   __device__ inline void fetch_v(int t) const {
-    dma_rows<4, 64, true>(c.vh, c.v_st, c.tile_base(t), nullptr, c.N, vbuf(t), wave, lane);
+    dma_rows<4, 64, true>(c.vh, c.v_st, c.dv, c.tile_base(t), nullptr, c.N, vbuf(t), wave, lane);
   }
   __device__ inline void fresh(f32x16 (&s)[2][2], int t, int cls) {
     if (cls == 2 || !has_ref)
@@ -615,7 +626,8 @@ __global__ __launch_bounds__(256) void ashape_kernel(QKV x, HeadList hl, int n_i
   const int NB = x.N / BQ;
   int slot, sb;
   if (!decode_wg(sched, slot, sb)) return;
-  const int head = hl.h[slot], kvh = head / x.group;
+  const int head = __builtin_amdgcn_readfirstlane(hl.h[slot]);
+  const int kvh = to_sgpr(head / x.group);
   const bf16_t *qh = x.q + head * x.q_sh;
   bf16_t *oh = x.o + head * x.o_sh;
 
@@ -640,6 +652,8 @@ __global__ __launch_bounds__(256) void ashape_kernel(QKV x, HeadList hl, int n_i
   AshapeCtx c;
   c.kh = x.k + kvh * x.k_sh; c.vh = x.v + kvh * x.v_sh; c.k_st = x.k_st; c.v_st = x.v_st;
   c.N = x.N; c.T1 = e1 / BK; c.T = c.T1 + (wq1 - s2) / BK; c.s2 = s2; c.lds = lds; c.c_log2 = x.c_log2;
+  dma_lane_init(c.dk, x.k_st, lane, wave);   // 4 cooperating waves: wave w only ever fetches blocks with blk % 4 == w
+  dma_lane_init(c.dv, x.v_st, lane, wave);
 
   ashape_pass_pipelined(c, st, lo, mp, wave, lane);
   if (__syncthreads_or(needs_exact(st) ? 1 : 0)) {
@@ -666,8 +680,11 @@ struct StepBuf {
 template <bool CONTIG>
 __device__ inline void fetch_step(const StepBuf &sb, int s, const bf16_t *kh, const bf16_t *vh, int64_t k_st,
                                   int64_t v_st, int kbase, const int *cols, int N, int lane) {
-  dma_rows<1, 32, CONTIG>(kh, k_st, kbase, cols, N, sb.k(s), 0, lane);
-  dma_rows<1, 32, CONTIG>(vh, v_st, kbase, cols, N, sb.v(s), 0, lane);
+  DmaLane dk, dv;
+  dma_lane_init(dk, k_st, lane);
+  dma_lane_init(dv, v_st, lane);
+  dma_rows<1, 32, CONTIG>(kh, k_st, dk, kbase, cols, N, sb.k(s), 0, lane);
+  dma_rows<1, 32, CONTIG>(vh, v_st, dv, kbase, cols, N, sb.v(s), 0, lane);
 }
 
 // Rare path on fresh logits of a gathered step: attended iff key <= query row.
@@ -719,14 +736,15 @@ struct WavePipe {
   int lane;
   Step d0, d1, d2;
   bool h0, h1, h2;
+  DmaLane dk, dv;
 
   __device__ inline void fetch_k(const Step &d, int slot) const {
-    if (GATHER) dma_rows<1, 32, false>(kh, k_st, 0, d.cols, N, buf.k(slot), 0, lane);
-    else dma_rows<1, 32, true>(kh, k_st, d.kbase, nullptr, N, buf.k(slot), 0, lane);
+    if (GATHER) dma_rows<1, 32, false>(kh, k_st, dk, 0, d.cols, N, buf.k(slot), 0, lane);
+    else dma_rows<1, 32, true>(kh, k_st, dk, d.kbase, nullptr, N, buf.k(slot), 0, lane);
   }
   __device__ inline void fetch_v(const Step &d, int slot) const {
-    if (GATHER) dma_rows<1, 32, false>(vh, v_st, 0, d.cols, N, buf.v(slot), 0, lane);
-    else dma_rows<1, 32, true>(vh, v_st, d.kbase, nullptr, N, buf.v(slot), 0, lane);
+    if (GATHER) dma_rows<1, 32, false>(vh, v_st, dv, 0, d.cols, N, buf.v(slot), 0, lane);
+    else dma_rows<1, 32, true>(vh, v_st, dv, d.kbase, nullptr, N, buf.v(slot), 0, lane);
   }
   __device__ inline void fresh(f32x16 (&s)[1][2], const Step &d) {
     if (d.cls == 2 || !has_ref) {
@@ -759,6 +777,8 @@ struct WavePipe {
     h2 = h2 && gen.next(d2);
   }
   __device__ inline void run() {
+    dma_lane_init(dk, k_st, lane);
+    dma_lane_init(dv, v_st, lane);
     h0 = gen.next(d0);
     h1 = h0 && gen.next(d1);
     h2 = h1 && gen.next(d2);
@@ -855,7 +875,8 @@ __global__ __launch_bounds__(64) void bs_kernel(QKV x, HeadList hl, const int32_
   const int NB = x.N / BQ;
   int slot, b;
   if (!decode_wg(sched, slot, b)) return;
-  const int head = hl.h[slot], kvh = head / x.group;
+  const int head = __builtin_amdgcn_readfirstlane(hl.h[slot]);
+  const int kvh = to_sgpr(head / x.group);
   const bf16_t *qh = x.q + head * x.q_sh;
   bf16_t *oh = x.o + head * x.o_sh;
   const int lane = threadIdx.x;
@@ -1104,7 +1125,8 @@ __global__ __launch_bounds__(64) void vs_kernel(QKV x, HeadList hl, const int32_
   const int NB = x.N / BQ;
   int slot, b;
   if (!decode_wg(sched, slot, b)) return;
-  const int head = hl.h[slot], kvh = head / x.group;
+  const int head = __builtin_amdgcn_readfirstlane(hl.h[slot]);
+  const int kvh = to_sgpr(head / x.group);
   const bf16_t *qh = x.q + head * x.q_sh;
   bf16_t *oh = x.o + head * x.o_sh;
   const int lane = threadIdx.x;

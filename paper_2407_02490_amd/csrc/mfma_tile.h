@@ -29,6 +29,19 @@ constexpr int K_TILE = BK * K_PITCH;
 
 __device__ inline float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Moves a wave-uniform value that the compiler computed on the vector ALU (an
+// integer division, say) into a scalar register, so that what is derived from
+// it (base pointers) is scalar work.  The builtin alone is folded away when the
+// compiler can prove uniformity and the value then stays in vector registers.
+// The compiler does not look inside the block, so the wait states that gfx950
+// requires between a vector write of v and v_readfirstlane reading it, and
+// between the scalar result and a memory instruction using it, are spelt out.
+__device__ inline int to_sgpr(int v) {
+  int s;
+  asm("s_nop 3\n\tv_readfirstlane_b32 %0, %1\n\ts_nop 4" : "=s"(s) : "v"(v));
+  return s;
+}
+
 // Row permutation applied when K rows are read as MFMA A-operand rows: MFMA
 // row m = 16t + 8u + 4h + w holds key 16t + 8h + 4u + w.  With it, the 8
 // accumulator registers 8t..8t+7 of lane-half h hold 8 consecutive keys
@@ -77,29 +90,44 @@ __device__ inline void dma16_su(const void *ubase, unsigned voff, unsigned lds_a
                :: "v"(voff), "s"(bs), "s"(a) : "memory");
 }
 
+// Per-lane constants of the tile fetch.  Row r = 4 blk + rl (rl = lane / 16) of a
+// tile lives in 1 KiB block blk; lane L holds chunk position cpos = L % 16, i.e.
+// the logical chunk cpos ^ f(r) = (cpos ^ (rl << 2)) ^ (blk & 3).  So the byte
+// offset of lane L's source inside block blk is
+//   4 blk row_bytes  (wave-uniform)  +  voff[blk & 3]  (per lane, fixed for the kernel).
+struct DmaLane {
+  unsigned voff[4];
+};
+// j0: added to the block residue; a wave that only ever fetches blocks with
+// blk % 4 == w passes j0 = w and uses voff[0].
+__device__ inline void dma_lane_init(DmaLane &d, int64_t stride, int lane, int j0 = 0) {
+  const unsigned rl = lane >> 4, cpos = lane & 15, row_bytes = (unsigned)stride * 2u;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) d.voff[j] = rl * row_bytes + (((cpos ^ (rl << 2)) ^ ((j + j0) & 3)) << 4);
+}
+
 // Fetch ROWS rows into the tile at `tile` (LDS).  NW waves cooperate: wave w
 // issues blocks w, w + NW, ...  CONTIG: rows are keys kbase + r; rows outside
 // [0, N) are clamped (the caller masks them); a step that lies wholly inside
-// [0, N) -- the common case -- takes the uniform-base form.  Otherwise keys come
-// from cols[r] in LDS (KEY_NONE reads row 0 and is masked by the caller).
-// stride * 2 * ROWS must fit 32 bits.
+// [0, N) -- the common case -- takes the uniform-base form, which costs scalar
+// ALU work only.  Otherwise keys come from cols[r] in LDS (KEY_NONE reads row 0
+// and is masked by the caller).  stride * 2 * 64 must fit 32 bits.
 template <int NW, int ROWS, bool CONTIG>
-__device__ inline void dma_rows(const bf16_t *g, int64_t stride, int kbase, const int *cols, int N,
-                                char *tile, int wave, int lane) {
-  const int rl = lane >> 4, cpos = lane & 15;
+__device__ inline void dma_rows(const bf16_t *g, int64_t stride, const DmaLane &dl, int kbase,
+                                const int *cols, int N, char *tile, int wave, int lane) {
   const unsigned base = lds_addr_of(tile);
   if (CONTIG && kbase >= 0 && kbase + ROWS <= N) {
     const bf16_t *ubase = g + (int64_t)kbase * stride;
-    const unsigned row_bytes = (unsigned)stride * 2u;
 #pragma unroll
     for (int i = 0; i < ROWS / 4 / NW; ++i) {
       const int blk = wave + NW * i;
-      const int r = 4 * blk + rl;
-      const int c = cpos ^ swz_f(r);
-      dma16_su(ubase, (unsigned)r * row_bytes + (unsigned)c * 16u, base + blk * 1024);
+      // NW == 4: blk & 3 == wave for every i; NW == 1: blk & 3 == i & 3 (compile time)
+      const unsigned voff = NW == 4 ? dl.voff[0] : dl.voff[i & 3];
+      dma16_su(ubase + (int64_t)(4 * blk) * stride, voff, base + blk * 1024);
     }
     return;
   }
+  const int rl = lane >> 4, cpos = lane & 15;
 #pragma unroll
   for (int i = 0; i < ROWS / 4 / NW; ++i) {
     const int blk = wave + NW * i;
