@@ -69,13 +69,20 @@ struct MaskP {
 // ---- per-wave setup / epilogue ---------------------------------------------
 __device__ inline void set_reference(WaveState &st, int nb, float m) { st.m[nb] = m; }
 
-__device__ inline void wave_init(WaveState &st, const bf16_t *qh, int64_t q_st, int q0, int lane) {
+__device__ inline void load_q(WaveState &st, const bf16_t *qh, int64_t q_st, int q0, int lane) {
   const int n = lane & 31, h = lane >> 5;
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb) {
     const bf16_t *row = qh + (int64_t)(q0 + 32 * nb + n) * q_st + 8 * h;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) st.q[nb][ks] = *reinterpret_cast<const bf16x8 *>(row + 16 * ks);
+  }
+}
+
+__device__ inline void wave_init(WaveState &st, const bf16_t *qh, int64_t q_st, int q0, int lane) {
+  load_q(st, qh, q_st, q0, lane);
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) {
     set_reference(st, nb, 0.f);
     st.l[nb] = 0.f;
   }
@@ -551,73 +558,260 @@ __device__ inline void ashape_pass(const AshapeCtx &c, WaveState &st, const Lane
   }
 }
 
-// Optimistic pass, software pipelined: while the vector ALU turns the logits of
-// tile t into P, the matrix cores already form the logits of tile t+1; then
-// P V of tile t.  K therefore runs one tile ahead of V through the two LDS
-// buffers of each: at the top of iteration t the wave issues the loads of
-// K(t+2) and V(t+1), which have a whole iteration to land.
+// K Q^T MFMA with the accumulator in ordinary vector registers and the Q operand
+// in accumulator registers.  The vector ALU cannot read accumulator registers
+// directly, and v_accvgpr_read runs on the matrix pipeline (measured: it queues
+// behind the MFMAs instead of overlapping them), so logits that the softmax is
+// to consume while MFMAs run must be produced in vector registers.  The compiler
+// picks one register class for all MFMA results of a kernel, hence assembly.
+// Wait states the compiler cannot see: a result is read by the vector ALU only
+// after at least four later MFMAs have issued (each occupies the pipeline for 8
+// passes), and by an MFMA on the same accumulator only after three others.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+__device__ inline void mfma_qk_first(f32x16 &acc, bf16x8 k, const i32x4 &q) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0"
+               : "=&v"(acc) : "a"(__builtin_bit_cast(i32x4, k)), "a"(q));
+}
+__device__ inline void mfma_qk_acc(f32x16 &acc, bf16x8 k, const i32x4 &q) {
+  asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
+               : "+v"(acc) : "a"(__builtin_bit_cast(i32x4, k)), "a"(q));
+}
+
+// Q operands of the pipelined pass, held in accumulator registers for the whole pass.
+struct QAcc {
+  i32x4 q[2][8];
+};
+__device__ inline void pin_q(QAcc &qa, const WaveState &st) {
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      qa.q[nb][ks] = __builtin_bit_cast(i32x4, st.q[nb][ks]);
+      asm volatile("" : "+a"(qa.q[nb][ks]));
+    }
+}
+
+// K Q^T of one tile into vector registers (start of the pipeline).
+__device__ inline void qk_tile_v(f32x16 (&s)[2][2], const QAcc &qa, const LaneOfs &lo, const char *tK) {
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb) {
+      const bf16x8 a = lds_read_k(tK, lo.k[ks] + mb * HALF_BYTES);
+      if (ks == 0) {
+        mfma_qk_first(s[mb][0], a, qa.q[0][0]);
+        mfma_qk_first(s[mb][1], a, qa.q[1][0]);
+      } else {
+        mfma_qk_acc(s[mb][0], a, qa.q[0][ks]);
+        mfma_qk_acc(s[mb][1], a, qa.q[1][ks]);
+      }
+    }
+  // the vector ALU may read s 18 wait states after the last MFMA was issued
+  asm volatile("s_nop 15\n\ts_nop 3" ::: "memory");
+}
+
+// What one wave contributes to the tile fetches of an iteration: block i of
+// its four K blocks goes out in round i, block i of its V blocks in round 4 + i
+// (eight loads issued back to back stall the wave for hundreds of cycles until
+// the memory pipeline has taken them).  Tiles lie wholly inside [0, N).
+struct RoundDma {
+  const bf16_t *k, *v;       // row 0 of the K / V tile to fetch, nullptr = none
+  int64_t k_st, v_st;
+  unsigned k_voff, v_voff;   // per lane
+  unsigned k_lds, v_lds;     // LDS byte address of the destination tile
+  int wave;
+  __device__ inline void issue(int r) const {
+    const int blk = wave + 4 * (r & 3);
+    if (r < 4) {
+      if (k) dma16_su(k + (int64_t)(4 * blk) * k_st, k_voff, k_lds + blk * 1024);
+    } else {
+      if (v) dma16_su(v + (int64_t)(4 * blk) * v_st, v_voff, v_lds + blk * 1024);
+    }
+  }
+};
+
+// Three tiles in flight per iteration of the optimistic pass.  The matrix
+// cores alternate between the logits of tile t+1 (K Q^T) and the output update
+// of tile t-1 (V^T P^T) while the vector ALU turns the logits of tile t into
+// P(t): all of the exp / convert / row-sum work runs in the shadow of MFMAs
+// that do not depend on it.  One iteration is cut into 8 rounds x 4 groups;
+// a group is {2 MFMAs; the LDS reads of operands needed later; 2 logits of
+// the softmax}.  sched_barrier(0) keeps the groups apart.
+__device__ inline void fused_qk_softmax_pv(f32x16 (&s_nxt)[2][2], bf16x8 (&p_cur)[2][2][2], WaveState &st,
+                                           const QAcc &qa, const f32x16 (&s_cur)[2][2],
+                                           const bf16x8 (&p_prev)[2][2][2],
+                                           const LaneOfs &lo, const char *tK, const char *tV, float c_log2,
+                                           bool attend_cur, const RoundDma &dma) {
+  // a tile this wave must not attend at all gets an infinite reference: P = exp2(-inf) = 0
+  const float m0 = attend_cur ? st.m[0] : INFINITY, m1 = attend_cur ? st.m[1] : INFINITY;
+  float lsum0 = 0.f, lsum1 = 0.f;
+  auto fetch_v = [&](int i) {            // PV step i = (mb, t, db)
+    const int mb = i / 8, t = (i / 4) & 1, db = i & 3;
+    const int base = (32 * mb + 16 * t) * ROW_BYTES;
+    return lds_read_vt(tV, lo.v[db][0] + base, lo.v[db][1] + base);
+  };
+  // Logits are walked so that round 2j + nb turns the 8 logits per lane of key
+  // group j = (mb, t) and query block nb into one B operand of the output
+  // update: P(t) group j is born in the rounds in which P(t-1) group j is last
+  // used, so the two generations of P share registers (about 40 instead of 64).
+  auto softmax2 = [&](int e) {           // e = 8 * round + 2 * group
+    const int j = e / 16, nb = (e / 8) & 1, mb = j / 2, r = 8 * (j & 1) + (e & 7);
+    const float m_use = nb == 0 ? m0 : m1;
+    const float e0 = fast_exp2(fmaf(s_cur[mb][nb][r], c_log2, -m_use));
+    const float e1 = fast_exp2(fmaf(s_cur[mb][nb][r + 1], c_log2, -m_use));
+    if (nb == 0) lsum0 += e0 + e1; else lsum1 += e0 + e1;
+    const f32x2 two = {e0, e1};
+    const bf16x2 b2 = __builtin_convertvector(two, bf16x2);
+    p_cur[nb][mb][r >> 3][r & 7] = b2[0];
+    p_cur[nb][mb][r >> 3][(r & 7) + 1] = b2[1];
+  };
+  constexpr int VA = 5;                  // V operands are fetched VA steps (2 VA MFMAs) ahead
+  bf16x8 ka[2], kn[2], va[16];
+  ka[0] = lds_read_k(tK, lo.k[0]);
+  ka[1] = lds_read_k(tK, lo.k[0] + HALF_BYTES);
+#pragma unroll
+  for (int i = 0; i < VA; ++i) va[i] = fetch_v(i);
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+    // group 0: logits of key block 0, k-step r
+    dma.issue(r);
+    if (r + 1 < 8) kn[0] = lds_read_k(tK, lo.k[r + 1]);
+    if (r == 0) {
+      mfma_qk_first(s_nxt[0][0], ka[0], qa.q[0][0]);
+      mfma_qk_first(s_nxt[0][1], ka[0], qa.q[1][0]);
+    } else {
+      mfma_qk_acc(s_nxt[0][0], ka[0], qa.q[0][r]);
+      mfma_qk_acc(s_nxt[0][1], ka[0], qa.q[1][r]);
+    }
+    softmax2(8 * r);
+    asm volatile("" : "+v"(lsum0), "+v"(lsum1));
+    __builtin_amdgcn_sched_barrier(0);
+    // group 1: key block 1
+    if (r + 1 < 8) kn[1] = lds_read_k(tK, lo.k[r + 1] + HALF_BYTES);
+    if (r == 0) {
+      mfma_qk_first(s_nxt[1][0], ka[1], qa.q[0][0]);
+      mfma_qk_first(s_nxt[1][1], ka[1], qa.q[1][0]);
+    } else {
+      mfma_qk_acc(s_nxt[1][0], ka[1], qa.q[0][r]);
+      mfma_qk_acc(s_nxt[1][1], ka[1], qa.q[1][r]);
+    }
+    softmax2(8 * r + 2);
+    asm volatile("" : "+v"(lsum0), "+v"(lsum1));
+    __builtin_amdgcn_sched_barrier(0);
+    // groups 2, 3: output update steps 2r, 2r + 1 of the previous tile
+#pragma unroll
+    for (int g = 0; g < 2; ++g) {
+      const int i = 2 * r + g;
+      if (i + VA < 16) va[i + VA] = fetch_v(i + VA);
+      const int mb = i / 8, t = (i / 4) & 1, db = i & 3;
+      st.o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i], p_prev[0][mb][t], st.o[db][0], 0, 0, 0);
+      st.o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i], p_prev[1][mb][t], st.o[db][1], 0, 0, 0);
+      softmax2(8 * r + 4 + 2 * g);
+      asm volatile("" : "+v"(lsum0), "+v"(lsum1));
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    ka[0] = kn[0];
+    ka[1] = kn[1];
+  }
+  if (attend_cur) {
+    st.l[0] += lsum0;
+    st.l[1] += lsum1;
+  }
+}
+
+// Optimistic pass, software pipelined three deep (see fused_qk_softmax_pv).
+// K and V each cycle through three LDS buffers; during iteration t the wave
+// issues its share of the loads of K(t+3) and V(t+1), which have two
+// iterations to land: iteration t reads K(t+1) and V(t-1).
+// Every wave runs the full iteration on every tile of the workgroup's key range,
+// also on tiles that lie wholly outside its own rows' mask (the four waves meet
+// at a barrier each iteration, so skipping would only idle): such a tile gets
+// P = 0.  The iteration body is one straight path, which keeps the 128
+// output accumulators in place; the first and the last iteration run it with a
+// zero P(-1) and on logits nobody consumes.
 struct AshapePipe {
   const AshapeCtx &c;
   WaveState &st;
+  const QAcc &qa;
   const LaneOfs &lo;
   const MaskP &mp;
   int wave, lane;
   bool has_ref;
   int cls_cur;
+  // LDS ring: k0 holds K(t+1), k1 K(t+2), k2 receives K(t+3); v0 holds V(t-1), v1 V(t), v2 receives V(t+1)
+  char *k0, *k1, *k2, *v0, *v1, *v2;
 
-  __device__ inline char *kbuf(int t) const { return c.lds + (t & 1) * TILE_BYTES; }
-  __device__ inline char *vbuf(int t) const { return c.lds + (2 + (t & 1)) * TILE_BYTES; }
-  __device__ inline void fetch_k(int t) const {
-    dma_rows<4, 64, true>(c.kh, c.k_st, c.dk, c.tile_base(t), nullptr, c.N, kbuf(t), wave, lane);
+  __device__ inline void fetch_k(int t, char *buf) const {
+    dma_rows<4, 64, true>(c.kh, c.k_st, c.dk, c.tile_base(t), nullptr, c.N, buf, wave, lane);
   }
-  __device__ inline void fetch_v(int t) const {
-    dma_rows<4, 64, true>(c.vh, c.v_st, c.dv, c.tile_base(t), nullptr, c.N, vbuf(t), wave, lane);
+  __device__ inline void fetch_v(int t, char *buf) const {
+    dma_rows<4, 64, true>(c.vh, c.v_st, c.dv, c.tile_base(t), nullptr, c.N, buf, wave, lane);
   }
   __device__ inline void fresh(f32x16 (&s)[2][2], int t, int cls) {
     if (cls == 2 || !has_ref)
       special_tile<2>(s, st, c.tile_base(t), mp, cls == 2, !has_ref, c.c_log2, lane);
     has_ref = true;
   }
-  // one iteration: s_cur holds the logits of tile t (if cls_cur), s_nxt receives tile t+1
-  __device__ inline void iter(int t, f32x16 (&s_cur)[2][2], f32x16 (&s_nxt)[2][2]) {
-    if (t + 2 < c.T) fetch_k(t + 2);
-    if (t + 1 < c.T) fetch_v(t + 1);
+  // iteration t in [0, T]: logits of tile t+1 into s_nxt, P(t) from s_cur into p_cur,
+  // output update of tile t-1 from p_prev
+  __device__ inline void iter(int t, f32x16 (&s_cur)[2][2], f32x16 (&s_nxt)[2][2], bf16x8 (&p_prev)[2][2][2],
+                              bf16x8 (&p_cur)[2][2][2]) {
+    int issued = 0;
+    RoundDma dma;
+    dma.k = nullptr; dma.v = nullptr;
+    dma.k_st = c.k_st; dma.v_st = c.v_st; dma.k_voff = c.dk.voff[0]; dma.v_voff = c.dv.voff[0];
+    dma.k_lds = lds_addr_of(k2); dma.v_lds = lds_addr_of(v2); dma.wave = wave;
+    if (t + 3 < c.T) { dma.k = c.kh + (int64_t)c.tile_base(t + 3) * c.k_st; issued += 4; }
+    if (t + 1 < c.T) { dma.v = c.vh + (int64_t)c.tile_base(t + 1) * c.v_st; issued += 4; }
     const int cls_nxt = t + 1 < c.T ? classify_step<64>(c.tile_base(t + 1), mp) : 0;
-    bf16x8 p[2][2][2];
-    if (cls_cur != 0 && cls_nxt != 0) {
-      fused_qk_softmax<2>(s_nxt, p, st, s_cur, lo, kbuf(t + 1), c.c_log2);
-    } else {
-      if (cls_nxt != 0) qk_tile<2>(s_nxt, st, lo, kbuf(t + 1));
-      if (cls_cur != 0) softmax_tile<2>(p, st, s_cur, c.c_log2);
-    }
+    // iteration 0 has no tile t-1: P(-1) = 0 times the (finite) rows of V(0)
+    fused_qk_softmax_pv(s_nxt, p_cur, st, qa, s_cur, p_prev, lo, k0, t == 0 ? v1 : v0, c.c_log2, cls_cur != 0, dma);
     if (cls_nxt != 0) fresh(s_nxt, t + 1, cls_nxt);
-    if (cls_cur != 0) pv_tile<2>(st, lo, vbuf(t), p);
     cls_cur = cls_nxt;
-    MINF_WAIT_VMCNT(0);
+    char *tk = k0; k0 = k1; k1 = k2; k2 = tk;
+    char *tv = v0; v0 = v1; v1 = v2; v2 = tv;
+    // everything but this iteration's own loads has landed
+    if (issued == 8) MINF_WAIT_VMCNT(8);
+    else if (issued == 4) MINF_WAIT_VMCNT(4);
+    else MINF_WAIT_VMCNT(0);
     __syncthreads();
   }
 };
 
 __device__ inline void ashape_pass_pipelined(const AshapeCtx &c, WaveState &st, const LaneOfs &lo,
                                              const MaskP &mp, int wave, int lane) {
-  AshapePipe pp{c, st, lo, mp, wave, lane, false, 0};
+  QAcc qa;
+  pin_q(qa, st);
+  AshapePipe pp{c, st, qa, lo, mp, wave, lane, false, 0};
+  // before iteration 0: k0 = K(0) .. k2 = K(2); V(0) in v1, so that after the rotation at the
+  // end of iteration 0 it is v0 = V(t-1) of iteration 1
+  pp.k0 = c.lds; pp.k1 = c.lds + TILE_BYTES; pp.k2 = c.lds + 2 * TILE_BYTES;
+  pp.v0 = c.lds + 3 * TILE_BYTES; pp.v1 = c.lds + 4 * TILE_BYTES; pp.v2 = c.lds + 5 * TILE_BYTES;
   f32x16 sa[2][2], sb[2][2];
-  pp.fetch_k(0);
-  if (c.T > 1) pp.fetch_k(1);
-  pp.fetch_v(0);
+  bf16x8 pa[2][2][2], pb[2][2][2];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) (&pa[0][0][0])[i][j] = (__bf16)0.f;
+  pp.fetch_k(0, pp.k0);
+  if (c.T > 1) pp.fetch_k(1, pp.k1);
+  if (c.T > 2) pp.fetch_k(2, pp.k2);
+  pp.fetch_v(0, pp.v1);
   MINF_WAIT_VMCNT(0);
   __syncthreads();
   pp.cls_cur = classify_step<64>(c.tile_base(0), mp);
-  if (pp.cls_cur != 0) {
-    qk_tile<2>(sa, st, lo, pp.kbuf(0));
-    pp.fresh(sa, 0, pp.cls_cur);
-  }
+  // also for a tile this wave does not attend: its (finite) logits are turned into P = 0
+  qk_tile_v(sa, qa, lo, pp.k0);
+  if (pp.cls_cur != 0) pp.fresh(sa, 0, pp.cls_cur);
+  // K(0) is consumed; rotate so that k0 = K(1), k1 = K(2), k2 = free
+  { char *tk = pp.k0; pp.k0 = pp.k1; pp.k1 = pp.k2; pp.k2 = tk; }
+  __syncthreads();   // all waves are done with K(0) before iteration 0 overwrites it with K(3)
   int t = 0;
-  for (; t + 1 < c.T; t += 2) {
-    pp.iter(t, sa, sb);
-    pp.iter(t + 1, sb, sa);
+  for (; t + 1 <= c.T; t += 2) {
+    pp.iter(t, sa, sb, pa, pb);
+    pp.iter(t + 1, sb, sa, pb, pa);
   }
-  if (t < c.T) pp.iter(t, sa, sb);
+  if (t <= c.T) pp.iter(t, sa, sb, pa, pb);
 }
 
 __global__ __launch_bounds__(256) void ashape_kernel(QKV x, HeadList hl, int n_init, int n_local,
@@ -657,6 +851,7 @@ __global__ __launch_bounds__(256) void ashape_kernel(QKV x, HeadList hl, int n_i
 
   ashape_pass_pipelined(c, st, lo, mp, wave, lane);
   if (__syncthreads_or(needs_exact(st) ? 1 : 0)) {
+    load_q(st, qh, x.q_st, q0, lane);   // the pipelined pass kept Q in accumulator registers only
     reset_for_max_pass(st);
     ashape_pass<PASS_MAX>(c, st, lo, mp, wave, lane);
     finish_max_pass(st, x.c_log2);
@@ -1169,7 +1364,7 @@ static hipError_t set_lds(const void *fn, size_t bytes) {
 hipError_t launch_ashape(const QKV &x, const HeadList &hl, int n_init, int n_local, hipStream_t st) {
   const int NB = x.N / BQ, NSB = (NB + 3) / 4;
   const Sched s = make_sched(hl.n, NSB);
-  const size_t lds = 4 * TILE_BYTES;
+  const size_t lds = 6 * TILE_BYTES;   // three K and three V buffers
   hipError_t e = set_lds(reinterpret_cast<const void *>(ashape_kernel), lds);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(ashape_kernel, dim3(s.per_xcd * 8), dim3(256), lds, st, x, hl, n_init, n_local, s);
