@@ -37,6 +37,8 @@
 //    shared by the 4 waves.  Block-Sparse / Vertical-Slash: tile lists differ
 //    per query block, so a workgroup is a single wave that streams 32-key
 //    steps through a private double buffer; 4 workgroups share a CU.
+#include <type_traits>
+
 #include "mfma_tile.h"
 
 namespace minf {
@@ -610,210 +612,283 @@ __device__ inline void qk_tile_v(f32x16 (&s)[2][2], const QAcc &qa, const LaneOf
   asm volatile("s_nop 15\n\ts_nop 3" ::: "memory");
 }
 
-// What one wave contributes to the tile fetches of an iteration: block i of
-// its four K blocks goes out in round i, block i of its V blocks in round 4 + i
-// (eight loads issued back to back stall the wave for hundreds of cycles until
-// the memory pipeline has taken them).  Tiles lie wholly inside [0, N).
-struct RoundDma {
-  const bf16_t *k, *v;       // row 0 of the K / V tile to fetch, nullptr = none
-  int64_t k_st, v_st;
-  unsigned k_voff, v_voff;   // per lane
-  unsigned k_lds, v_lds;     // LDS byte address of the destination tile
-  int wave;
-  __device__ inline void issue(int r) const {
-    const int blk = wave + 4 * (r & 3);
-    if (r < 4) {
-      if (k) dma16_su(k + (int64_t)(4 * blk) * k_st, k_voff, k_lds + blk * 1024);
-    } else {
-      if (v) dma16_su(v + (int64_t)(4 * blk) * v_st, v_voff, v_lds + blk * 1024);
-    }
+// This wave's quarter of the fetch of a 64-row tile that lies wholly inside
+// [0, N): rows 16w .. 16w+15, i.e. the 1 KiB blocks 4w .. 4w+3 of the tile in LDS.
+// ROWS256: rows are 256 bytes apart in global memory as they are in LDS, so the
+// four blocks are 1 KiB apart on both sides and one base pair and one M0 value
+// serve all four loads through the instruction's immediate offset (it shifts the
+// global and the LDS address alike).  Otherwise each block gets its own base.
+struct WaveDma {
+  unsigned k_voff[4], v_voff[4];   // per lane, block 4w + i
+  unsigned k_rb, v_rb;             // bytes between rows
+  const char *kw, *vw;             // head base + 16 w rows
+  unsigned lds_w;                  // 4 w KiB
+};
+template <int I>
+__device__ inline void dma16_imm(const char *ubase, unsigned voff, unsigned lds_addr) {
+  if (I == 0) asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" :: "v"(voff), "s"(ubase), "s"(lds_addr) : "memory");
+  if (I == 1) asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 offset:1024" :: "v"(voff), "s"(ubase), "s"(lds_addr) : "memory");
+  if (I == 2) asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 offset:2048" :: "v"(voff), "s"(ubase), "s"(lds_addr) : "memory");
+  if (I == 3) asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 offset:3072" :: "v"(voff), "s"(ubase), "s"(lds_addr) : "memory");
+}
+template <bool ROWS256, int I>
+__device__ inline void dma_block(const char *tile_w, unsigned rb, unsigned voff, unsigned lds_tile_w) {
+  if (ROWS256) dma16_imm<I>(tile_w, voff, lds_tile_w);
+  else dma16_imm<0>(tile_w + (size_t)(4 * I) * rb, voff, lds_tile_w + I * 1024);
+}
+
+// Class of the 64-key tile at kb for the wave whose rows are q0 .. q0+63 under
+// the A-shape mask, with the comparisons' constants taken out of the loop:
+// 0 = nothing to attend, 1 = all attended, 2 = mixed.
+struct AshapeCls {
+  int qlast, n_init, a, b, c, d;
+  __device__ inline void init(const MaskP &mp) {
+    qlast = mp.q0 + BQ - 1; n_init = mp.n_init;
+    a = mp.q0 - (BK - 1) - mp.n_local;   // kb <= a: the tile ends before the window of the first row starts
+    b = mp.q0 - (BK - 1);                // kb <= b: the tile ends at or before the first row (no causal cut)
+    c = mp.n_init - (BK - 1);            // kb <  c: the tile lies inside the sink
+    d = qlast - mp.n_local;              // kb >  d: the tile starts inside the window of the last row
+  }
+  __device__ inline int of(int kb) const {
+    if (kb > qlast || (kb >= n_init && kb <= a)) return 0;
+    return (kb <= b && (kb < c || kb > d)) ? 1 : 2;
   }
 };
 
-// Three tiles in flight per iteration of the optimistic pass.  The matrix
-// cores alternate between the logits of tile t+1 (K Q^T) and the output update
-// of tile t-1 (V^T P^T) while the vector ALU turns the logits of tile t into
-// P(t): all of the exp / convert / row-sum work runs in the shadow of MFMAs
-// that do not depend on it.  One iteration is cut into 8 rounds x 4 groups;
-// a group is {2 MFMAs; the LDS reads of operands needed later; 2 logits of
-// the softmax}.  sched_barrier(0) keeps the groups apart.
-__device__ inline void fused_qk_softmax_pv(f32x16 (&s_nxt)[2][2], bf16x8 (&p_cur)[2][2][2], WaveState &st,
-                                           const QAcc &qa, const f32x16 (&s_cur)[2][2],
-                                           const bf16x8 (&p_prev)[2][2][2],
-                                           const LaneOfs &lo, const char *tK, const char *tV, float c_log2,
-                                           bool attend_cur, const RoundDma &dma) {
-  // a tile this wave must not attend at all gets an infinite reference: P = exp2(-inf) = 0
-  const float m0 = attend_cur ? st.m[0] : INFINITY, m1 = attend_cur ? st.m[1] : INFINITY;
-  float lsum0 = 0.f, lsum1 = 0.f;
-  auto fetch_v = [&](int i) {            // PV step i = (mb, t, db)
-    const int mb = i / 8, t = (i / 4) & 1, db = i & 3;
-    const int base = (32 * mb + 16 * t) * ROW_BYTES;
-    return lds_read_vt(tV, lo.v[db][0] + base, lo.v[db][1] + base);
-  };
-  // Logits are walked so that round 2j + nb turns the 8 logits per lane of key
-  // group j = (mb, t) and query block nb into one B operand of the output
-  // update: P(t) group j is born in the rounds in which P(t-1) group j is last
-  // used, so the two generations of P share registers (about 40 instead of 64).
-  auto softmax2 = [&](int e) {           // e = 8 * round + 2 * group
-    const int j = e / 16, nb = (e / 8) & 1, mb = j / 2, r = 8 * (j & 1) + (e & 7);
-    const float m_use = nb == 0 ? m0 : m1;
-    const float e0 = fast_exp2(fmaf(s_cur[mb][nb][r], c_log2, -m_use));
-    const float e1 = fast_exp2(fmaf(s_cur[mb][nb][r + 1], c_log2, -m_use));
-    if (nb == 0) lsum0 += e0 + e1; else lsum1 += e0 + e1;
-    const f32x2 two = {e0, e1};
-    const bf16x2 b2 = __builtin_convertvector(two, bf16x2);
-    p_cur[nb][mb][r >> 3][r & 7] = b2[0];
-    p_cur[nb][mb][r >> 3][(r & 7) + 1] = b2[1];
-  };
-  constexpr int VA = 5;                  // V operands are fetched VA steps (2 VA MFMAs) ahead
-  bf16x8 ka[2], kn[2], va[16];
-  ka[0] = lds_read_k(tK, lo.k[0]);
-  ka[1] = lds_read_k(tK, lo.k[0] + HALF_BYTES);
-#pragma unroll
-  for (int i = 0; i < VA; ++i) va[i] = fetch_v(i);
-#pragma unroll
-  for (int r = 0; r < 8; ++r) {
-    // group 0: logits of key block 0, k-step r
-    dma.issue(r);
-    if (r + 1 < 8) kn[0] = lds_read_k(tK, lo.k[r + 1]);
-    if (r == 0) {
-      mfma_qk_first(s_nxt[0][0], ka[0], qa.q[0][0]);
-      mfma_qk_first(s_nxt[0][1], ka[0], qa.q[1][0]);
-    } else {
-      mfma_qk_acc(s_nxt[0][0], ka[0], qa.q[0][r]);
-      mfma_qk_acc(s_nxt[0][1], ka[0], qa.q[1][r]);
-    }
-    softmax2(8 * r);
-    asm volatile("" : "+v"(lsum0), "+v"(lsum1));
-    __builtin_amdgcn_sched_barrier(0);
-    // group 1: key block 1
-    if (r + 1 < 8) kn[1] = lds_read_k(tK, lo.k[r + 1] + HALF_BYTES);
-    if (r == 0) {
-      mfma_qk_first(s_nxt[1][0], ka[1], qa.q[0][0]);
-      mfma_qk_first(s_nxt[1][1], ka[1], qa.q[1][0]);
-    } else {
-      mfma_qk_acc(s_nxt[1][0], ka[1], qa.q[0][r]);
-      mfma_qk_acc(s_nxt[1][1], ka[1], qa.q[1][r]);
-    }
-    softmax2(8 * r + 2);
-    asm volatile("" : "+v"(lsum0), "+v"(lsum1));
-    __builtin_amdgcn_sched_barrier(0);
-    // groups 2, 3: output update steps 2r, 2r + 1 of the previous tile
-#pragma unroll
-    for (int g = 0; g < 2; ++g) {
-      const int i = 2 * r + g;
-      if (i + VA < 16) va[i + VA] = fetch_v(i + VA);
-      const int mb = i / 8, t = (i / 4) & 1, db = i & 3;
-      st.o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i], p_prev[0][mb][t], st.o[db][0], 0, 0, 0);
-      st.o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[i], p_prev[1][mb][t], st.o[db][1], 0, 0, 0);
-      softmax2(8 * r + 4 + 2 * g);
-      asm volatile("" : "+v"(lsum0), "+v"(lsum1));
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    ka[0] = kn[0];
-    ka[1] = kn[1];
-  }
-  if (attend_cur) {
-    st.l[0] += lsum0;
-    st.l[1] += lsum1;
-  }
-}
-
-// Optimistic pass, software pipelined three deep (see fused_qk_softmax_pv).
-// K and V each cycle through three LDS buffers; during iteration t the wave
-// issues its share of the loads of K(t+3) and V(t+1), which have two
-// iterations to land: iteration t reads K(t+1) and V(t-1).
-// Every wave runs the full iteration on every tile of the workgroup's key range,
-// also on tiles that lie wholly outside its own rows' mask (the four waves meet
-// at a barrier each iteration, so skipping would only idle): such a tile gets
-// P = 0.  The iteration body is one straight path, which keeps the 128
-// output accumulators in place; the first and the last iteration run it with a
-// zero P(-1) and on logits nobody consumes.
-struct AshapePipe {
-  const AshapeCtx &c;
+// Optimistic pass of the shared-tile kernel, software pipelined three deep.
+// Iteration t: the matrix cores alternate between the logits of tile t+1
+// (K Q^T) and the output update of tile t-1 (V^T P^T) while the vector ALU turns
+// the logits of tile t into P(t), so all exp / convert / row-sum work runs in
+// the shadow of MFMAs that do not depend on it.  With one wave per SIMD the wave
+// issues at most one instruction every four cycles, so the iteration is built
+// to a budget of instructions: about 9 per MFMA all told.
+//  - One iteration = 8 rounds x 4 groups; a group is 2 MFMAs and 2 logits of the
+//    softmax.  The LDS reads of a round's operands are issued as one batch at
+//    the top of the round before (one wait per round); the wave's 8 tile loads
+//    go out one per round (back to back they stall the wave until the memory
+//    pipeline has taken them); scalar bookkeeping sits between the rounds' MFMAs.
+//  - K and V each cycle through three LDS buffers; iteration t issues the loads
+//    of K(t+3) and V(t+1), which have two iterations to land, and reads K(t+1)
+//    and V(t-1).  Slot of tile i: i mod 3.  Past the last tile the loads repeat
+//    it into the free slot, so that every iteration issues 8 loads and one
+//    constant wait count serves.
+//  - Every wave runs every iteration on every tile of the workgroup's key range,
+//    also on tiles outside its own rows' mask (the four waves meet at a barrier
+//    each iteration, so skipping would only idle): such a tile gets P = 0 via an
+//    infinite reference.  The body is one straight path, which keeps the 128
+//    output accumulators in place; the first iteration multiplies a zero P(-1)
+//    with V(0), the last two form logits nobody consumes.
+template <bool ROWS256>
+struct AshapeLoop {
   WaveState &st;
   const QAcc &qa;
   const LaneOfs &lo;
   const MaskP &mp;
-  int wave, lane;
-  bool has_ref;
+  const WaveDma &d;
+  AshapeCls cls;
+  float c_log2;
+  int lane;
+  int T, T1, s2;
+  char *lds;                 // K slots at lds + i * 16 KiB, V slots at lds + (3 + i) * 16 KiB
+  unsigned ra, rb, rc;       // ring: byte offsets of slots t mod 3, (t+1) mod 3, (t+2) mod 3
+  int kb1, kb2, kb3, ti3;    // key bases of tiles t+1, t+2, t+3 (indices clamped to T-1); index of the last
   int cls_cur;
-  // LDS ring: k0 holds K(t+1), k1 K(t+2), k2 receives K(t+3); v0 holds V(t-1), v1 V(t), v2 receives V(t+1)
-  char *k0, *k1, *k2, *v0, *v1, *v2;
+  bool has_ref;
 
-  __device__ inline void fetch_k(int t, char *buf) const {
-    dma_rows<4, 64, true>(c.kh, c.k_st, c.dk, c.tile_base(t), nullptr, c.N, buf, wave, lane);
+  // scalar operands of the coming iteration
+  const char *kt_, *vt_, *tK_, *tV_;
+  unsigned k_dst_, v_dst_;
+  int cls_nxt_;
+
+  __device__ inline int tile_base(int i) const { return i < T1 ? i * BK : s2 + (i - T1) * BK; }
+
+  // for iteration t, from the ring and tile state of iteration t
+  __device__ inline void prepare(int t) {
+    kt_ = d.kw + (size_t)kb3 * d.k_rb;                                  // K(t+3) -> slot t mod 3
+    vt_ = d.vw + (size_t)kb1 * d.v_rb;                                  // V(t+1) -> slot (t+1) mod 3
+    k_dst_ = lds_addr_of(lds) + ra + d.lds_w;
+    v_dst_ = lds_addr_of(lds) + 3 * TILE_BYTES + rb + d.lds_w;
+    tK_ = lds + rb;                                                     // K(t+1)
+    tV_ = lds + 3 * TILE_BYTES + (t == 0 ? ra : rc);                    // V(t-1); V(0) for the zero P(-1)
+    cls_nxt_ = t + 1 < T ? cls.of(kb1) : 0;
   }
-  __device__ inline void fetch_v(int t, char *buf) const {
-    dma_rows<4, 64, true>(c.vh, c.v_st, c.dv, c.tile_base(t), nullptr, c.N, buf, wave, lane);
+
+  template <int I>
+  __device__ inline void load_k(int kb, unsigned slot_ofs) const {
+    dma_block<ROWS256, I>(d.kw + (size_t)kb * d.k_rb, d.k_rb, d.k_voff[I], lds_addr_of(lds) + slot_ofs + d.lds_w);
   }
-  __device__ inline void fresh(f32x16 (&s)[2][2], int t, int cls) {
-    if (cls == 2 || !has_ref)
-      special_tile<2>(s, st, c.tile_base(t), mp, cls == 2, !has_ref, c.c_log2, lane);
-    has_ref = true;
+  template <int I>
+  __device__ inline void load_v(int kb, unsigned slot_ofs) const {
+    dma_block<ROWS256, I>(d.vw + (size_t)kb * d.v_rb, d.v_rb, d.v_voff[I],
+                          lds_addr_of(lds) + 3 * TILE_BYTES + slot_ofs + d.lds_w);
   }
-  // iteration t in [0, T]: logits of tile t+1 into s_nxt, P(t) from s_cur into p_cur,
-  // output update of tile t-1 from p_prev
+  template <int R>
+  __device__ inline void round_dma(const char *kt, const char *vt, unsigned k_dst, unsigned v_dst) const {
+    if (R < 4) dma_block<ROWS256, R & 3>(kt, d.k_rb, d.k_voff[R & 3], k_dst);
+    else dma_block<ROWS256, R & 3>(vt, d.v_rb, d.v_voff[R & 3], v_dst);
+  }
+
   __device__ inline void iter(int t, f32x16 (&s_cur)[2][2], f32x16 (&s_nxt)[2][2], bf16x8 (&p_prev)[2][2][2],
                               bf16x8 (&p_cur)[2][2][2]) {
-    int issued = 0;
-    RoundDma dma;
-    dma.k = nullptr; dma.v = nullptr;
-    dma.k_st = c.k_st; dma.v_st = c.v_st; dma.k_voff = c.dk.voff[0]; dma.v_voff = c.dv.voff[0];
-    dma.k_lds = lds_addr_of(k2); dma.v_lds = lds_addr_of(v2); dma.wave = wave;
-    if (t + 3 < c.T) { dma.k = c.kh + (int64_t)c.tile_base(t + 3) * c.k_st; issued += 4; }
-    if (t + 1 < c.T) { dma.v = c.vh + (int64_t)c.tile_base(t + 1) * c.v_st; issued += 4; }
-    const int cls_nxt = t + 1 < c.T ? classify_step<64>(c.tile_base(t + 1), mp) : 0;
-    // iteration 0 has no tile t-1: P(-1) = 0 times the (finite) rows of V(0)
-    fused_qk_softmax_pv(s_nxt, p_cur, st, qa, s_cur, p_prev, lo, k0, t == 0 ? v1 : v0, c.c_log2, cls_cur != 0, dma);
-    if (cls_nxt != 0) fresh(s_nxt, t + 1, cls_nxt);
+    const char *tK = tK_, *tV = tV_;
+    auto fetch_v = [&](int i) {            // PV step i = (mb, t, db)
+      const int mb = i / 8, tt = (i / 4) & 1, db = i & 3;
+      const int base = (32 * mb + 16 * tt) * ROW_BYTES;
+      return lds_read_vt(tV, lo.v[db][0] + base, lo.v[db][1] + base);
+    };
+    bf16x8 kf[8][2], vf[16];
+    kf[0][0] = lds_read_k(tK, lo.k[0]);
+    kf[0][1] = lds_read_k(tK, lo.k[0] + HALF_BYTES);
+    vf[0] = fetch_v(0);
+    vf[1] = fetch_v(1);
+    // the iteration's scalar operands were prepared during the previous one
+    const char *kt = kt_, *vt = vt_;
+    const unsigned k_dst = k_dst_, v_dst = v_dst_;
+    const int cls_nxt = cls_nxt_, kb_nxt = kb1;
+    const bool attend_cur = cls_cur != 0;
+    // ... and the next one's are prepared in round 5, between MFMAs
+    auto prepare_next = [&]() {
+      const unsigned r0 = ra; ra = rb; rb = rc; rc = r0;
+      kb1 = kb2; kb2 = kb3;
+      if (ti3 + 1 < T) {
+        ++ti3;
+        kb3 = ti3 == T1 ? s2 : kb3 + BK;
+      }
+      prepare(t + 1);
+    };
+    // a tile this wave must not attend at all gets an infinite reference: P = exp2(-inf) = 0
+    const float m0 = attend_cur ? st.m[0] : INFINITY, m1 = attend_cur ? st.m[1] : INFINITY;
+    float lsum0 = 0.f, lsum1 = 0.f;
+    // Logits are walked so that round 2j + nb turns the 8 logits per lane of key
+    // group j = (mb, t) and query block nb into one B operand of the output
+    // update: P(t) group j is born in the rounds in which P(t-1) group j is last
+    // used, so the two generations of P share registers (about 40 instead of 64).
+    auto softmax2 = [&](int e) {           // e = 8 * round + 2 * group
+      const int j = e / 16, nb = (e / 8) & 1, mb = j / 2, r = 8 * (j & 1) + (e & 7);
+      const float m_use = nb == 0 ? m0 : m1;
+      const float e0 = fast_exp2(fmaf(s_cur[mb][nb][r], c_log2, -m_use));
+      const float e1 = fast_exp2(fmaf(s_cur[mb][nb][r + 1], c_log2, -m_use));
+      if (nb == 0) lsum0 += e0 + e1; else lsum1 += e0 + e1;
+      const f32x2 two = {e0, e1};
+      unsigned pk = __builtin_bit_cast(unsigned, __builtin_convertvector(two, bf16x2));
+      asm volatile("" : "+v"(pk));         // convert here, not where P is consumed an iteration later
+      const bf16x2 b2 = __builtin_bit_cast(bf16x2, pk);
+      p_cur[nb][mb][r >> 3][r & 7] = b2[0];
+      p_cur[nb][mb][r >> 3][(r & 7) + 1] = b2[1];
+    };
+    auto round = [&](auto rc_) {
+      constexpr int r = decltype(rc_)::value;
+      if (r + 1 < 8) {
+        kf[(r + 1) & 7][0] = lds_read_k(tK, lo.k[(r + 1) & 7]);
+        kf[(r + 1) & 7][1] = lds_read_k(tK, lo.k[(r + 1) & 7] + HALF_BYTES);
+        vf[(2 * r + 2) & 15] = fetch_v((2 * r + 2) & 15);
+        vf[(2 * r + 3) & 15] = fetch_v((2 * r + 3) & 15);
+        // one wait per round: everything but the 6 reads just issued (this round's operands
+        // went out a round ago); vmcnt and expcnt fields are left open
+        __builtin_amdgcn_s_waitcnt(0xC67F);
+      } else {
+        __builtin_amdgcn_s_waitcnt(0xC07F);
+      }
+      round_dma<r>(kt, vt, k_dst, v_dst);
+      if (r == 5) prepare_next();
+      // groups 0, 1: logits of key blocks 0, 1, k-step r
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb) {
+        if (r == 0) {
+          mfma_qk_first(s_nxt[mb][0], kf[0][mb], qa.q[0][0]);
+          mfma_qk_first(s_nxt[mb][1], kf[0][mb], qa.q[1][0]);
+        } else {
+          mfma_qk_acc(s_nxt[mb][0], kf[r][mb], qa.q[0][r]);
+          mfma_qk_acc(s_nxt[mb][1], kf[r][mb], qa.q[1][r]);
+        }
+        softmax2(8 * r + 2 * mb);
+        asm volatile("" : "+v"(lsum0), "+v"(lsum1));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // groups 2, 3: output update steps 2r, 2r + 1 of the previous tile
+#pragma unroll
+      for (int g = 0; g < 2; ++g) {
+        const int i = 2 * r + g;
+        const int mb = i / 8, tt = (i / 4) & 1, db = i & 3;
+        st.o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], p_prev[0][mb][tt], st.o[db][0], 0, 0, 0);
+        st.o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], p_prev[1][mb][tt], st.o[db][1], 0, 0, 0);
+        softmax2(8 * r + 4 + 2 * g);
+        asm volatile("" : "+v"(lsum0), "+v"(lsum1));
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    };
+    round(std::integral_constant<int, 0>{});
+    round(std::integral_constant<int, 1>{});
+    round(std::integral_constant<int, 2>{});
+    round(std::integral_constant<int, 3>{});
+    round(std::integral_constant<int, 4>{});
+    round(std::integral_constant<int, 5>{});
+    round(std::integral_constant<int, 6>{});
+    round(std::integral_constant<int, 7>{});
+    if (attend_cur) {
+      st.l[0] += lsum0;
+      st.l[1] += lsum1;
+    }
+    // logits of tile t+1: element mask and / or the exponent reference (rare)
+    if (cls_nxt == 2 || (cls_nxt != 0 && !has_ref)) {
+      special_tile<2>(s_nxt, st, kb_nxt, mp, cls_nxt == 2, !has_ref, c_log2, lane);
+      has_ref = true;
+    }
     cls_cur = cls_nxt;
-    char *tk = k0; k0 = k1; k1 = k2; k2 = tk;
-    char *tv = v0; v0 = v1; v1 = v2; v2 = tv;
-    // everything but this iteration's own loads has landed
-    if (issued == 8) MINF_WAIT_VMCNT(8);
-    else if (issued == 4) MINF_WAIT_VMCNT(4);
-    else MINF_WAIT_VMCNT(0);
+    MINF_WAIT_VMCNT(8);     // everything but this iteration's own 8 loads has landed
     __syncthreads();
   }
 };
 
-__device__ inline void ashape_pass_pipelined(const AshapeCtx &c, WaveState &st, const LaneOfs &lo,
-                                             const MaskP &mp, int wave, int lane) {
+template <bool ROWS256>
+__device__ inline void ashape_pass_pipelined(const AshapeCtx &c, const WaveDma &d, WaveState &st,
+                                             const LaneOfs &lo, const MaskP &mp, int lane) {
   QAcc qa;
   pin_q(qa, st);
-  AshapePipe pp{c, st, qa, lo, mp, wave, lane, false, 0};
-  // before iteration 0: k0 = K(0) .. k2 = K(2); V(0) in v1, so that after the rotation at the
-  // end of iteration 0 it is v0 = V(t-1) of iteration 1
-  pp.k0 = c.lds; pp.k1 = c.lds + TILE_BYTES; pp.k2 = c.lds + 2 * TILE_BYTES;
-  pp.v0 = c.lds + 3 * TILE_BYTES; pp.v1 = c.lds + 4 * TILE_BYTES; pp.v2 = c.lds + 5 * TILE_BYTES;
+  AshapeLoop<ROWS256> lp{st, qa, lo, mp, d};
+  lp.cls.init(mp);
+  lp.c_log2 = c.c_log2; lp.lane = lane; lp.T = c.T; lp.T1 = c.T1; lp.s2 = c.s2; lp.lds = c.lds;
+  lp.ra = 0; lp.rb = TILE_BYTES; lp.rc = 2 * TILE_BYTES;
+  lp.has_ref = false;
+  const int last = c.T - 1;
+  const int kb0 = lp.tile_base(0);
+  lp.kb1 = lp.tile_base(min(1, last)); lp.kb2 = lp.tile_base(min(2, last));
+  lp.ti3 = min(3, last); lp.kb3 = lp.tile_base(lp.ti3);
   f32x16 sa[2][2], sb[2][2];
   bf16x8 pa[2][2][2], pb[2][2][2];
 #pragma unroll
   for (int i = 0; i < 8; ++i)
 #pragma unroll
     for (int j = 0; j < 8; ++j) (&pa[0][0][0])[i][j] = (__bf16)0.f;
-  pp.fetch_k(0, pp.k0);
-  if (c.T > 1) pp.fetch_k(1, pp.k1);
-  if (c.T > 2) pp.fetch_k(2, pp.k2);
-  pp.fetch_v(0, pp.v1);
+  // K(0), K(1), K(2) into K slots 0, 1, 2 and V(0) into V slot 0
+  lp.template load_k<0>(kb0, 0); lp.template load_k<1>(kb0, 0); lp.template load_k<2>(kb0, 0); lp.template load_k<3>(kb0, 0);
+  lp.template load_k<0>(lp.kb1, TILE_BYTES); lp.template load_k<1>(lp.kb1, TILE_BYTES);
+  lp.template load_k<2>(lp.kb1, TILE_BYTES); lp.template load_k<3>(lp.kb1, TILE_BYTES);
+  lp.template load_k<0>(lp.kb2, 2 * TILE_BYTES); lp.template load_k<1>(lp.kb2, 2 * TILE_BYTES);
+  lp.template load_k<2>(lp.kb2, 2 * TILE_BYTES); lp.template load_k<3>(lp.kb2, 2 * TILE_BYTES);
+  lp.template load_v<0>(kb0, 0); lp.template load_v<1>(kb0, 0); lp.template load_v<2>(kb0, 0); lp.template load_v<3>(kb0, 0);
   MINF_WAIT_VMCNT(0);
   __syncthreads();
-  pp.cls_cur = classify_step<64>(c.tile_base(0), mp);
+  lp.cls_cur = lp.cls.of(kb0);
   // also for a tile this wave does not attend: its (finite) logits are turned into P = 0
-  qk_tile_v(sa, qa, lo, pp.k0);
-  if (pp.cls_cur != 0) pp.fresh(sa, 0, pp.cls_cur);
-  // K(0) is consumed; rotate so that k0 = K(1), k1 = K(2), k2 = free
-  { char *tk = pp.k0; pp.k0 = pp.k1; pp.k1 = pp.k2; pp.k2 = tk; }
+  qk_tile_v(sa, qa, lo, c.lds);
+  if (lp.cls_cur != 0) {
+    special_tile<2>(sa, st, kb0, mp, lp.cls_cur == 2, true, c.c_log2, lane);
+    lp.has_ref = true;
+  }
   __syncthreads();   // all waves are done with K(0) before iteration 0 overwrites it with K(3)
+  lp.prepare(0);
   int t = 0;
   for (; t + 1 <= c.T; t += 2) {
-    pp.iter(t, sa, sb, pa, pb);
-    pp.iter(t + 1, sb, sa, pb, pa);
+    lp.iter(t, sa, sb, pa, pb);
+    lp.iter(t + 1, sb, sa, pb, pa);
   }
-  if (t <= c.T) pp.iter(t, sa, sb, pa, pb);
+  if (t <= c.T) lp.iter(t, sa, sb, pa, pb);
+  MINF_WAIT_VMCNT(0);   // the repeated loads of the last iterations
+  __syncthreads();
 }
 
+template <bool ROWS256>
 __global__ __launch_bounds__(256) void ashape_kernel(QKV x, HeadList hl, int n_init, int n_local,
                                                      Sched sched) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -846,10 +921,17 @@ __global__ __launch_bounds__(256) void ashape_kernel(QKV x, HeadList hl, int n_i
   AshapeCtx c;
   c.kh = x.k + kvh * x.k_sh; c.vh = x.v + kvh * x.v_sh; c.k_st = x.k_st; c.v_st = x.v_st;
   c.N = x.N; c.T1 = e1 / BK; c.T = c.T1 + (wq1 - s2) / BK; c.s2 = s2; c.lds = lds; c.c_log2 = x.c_log2;
-  dma_lane_init(c.dk, x.k_st, lane, wave);   // 4 cooperating waves: wave w only ever fetches blocks with blk % 4 == w
-  dma_lane_init(c.dv, x.v_st, lane, wave);
+  dma_lane_init(c.dk, x.k_st, lane);
+  dma_lane_init(c.dv, x.v_st, lane);
+  WaveDma d;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) { d.k_voff[i] = c.dk.voff[i]; d.v_voff[i] = c.dv.voff[i]; }
+  d.k_rb = (unsigned)x.k_st * 2u; d.v_rb = (unsigned)x.v_st * 2u;
+  d.kw = reinterpret_cast<const char *>(c.kh) + (size_t)(16 * wave) * d.k_rb;
+  d.vw = reinterpret_cast<const char *>(c.vh) + (size_t)(16 * wave) * d.v_rb;
+  d.lds_w = wave * 4096;
 
-  ashape_pass_pipelined(c, st, lo, mp, wave, lane);
+  ashape_pass_pipelined<ROWS256>(c, d, st, lo, mp, lane);
   if (__syncthreads_or(needs_exact(st) ? 1 : 0)) {
     load_q(st, qh, x.q_st, q0, lane);   // the pipelined pass kept Q in accumulator registers only
     reset_for_max_pass(st);
@@ -1365,9 +1447,16 @@ hipError_t launch_ashape(const QKV &x, const HeadList &hl, int n_init, int n_loc
   const int NB = x.N / BQ, NSB = (NB + 3) / 4;
   const Sched s = make_sched(hl.n, NSB);
   const size_t lds = 6 * TILE_BYTES;   // three K and three V buffers
-  hipError_t e = set_lds(reinterpret_cast<const void *>(ashape_kernel), lds);
+  // rows 256 bytes apart in both K and V (the [head][token][128] layout): cheaper tile fetch
+  const bool rows256 = x.k_st == D && x.v_st == D;
+  const void *fn = rows256 ? reinterpret_cast<const void *>(ashape_kernel<true>)
+                           : reinterpret_cast<const void *>(ashape_kernel<false>);
+  hipError_t e = set_lds(fn, lds);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(ashape_kernel, dim3(s.per_xcd * 8), dim3(256), lds, st, x, hl, n_init, n_local, s);
+  if (rows256)
+    hipLaunchKernelGGL(ashape_kernel<true>, dim3(s.per_xcd * 8), dim3(256), lds, st, x, hl, n_init, n_local, s);
+  else
+    hipLaunchKernelGGL(ashape_kernel<false>, dim3(s.per_xcd * 8), dim3(256), lds, st, x, hl, n_init, n_local, s);
   return hipGetLastError();
 }
 

@@ -98,16 +98,14 @@ __device__ inline void dma16_su(const void *ubase, unsigned voff, unsigned lds_a
 struct DmaLane {
   unsigned voff[4];
 };
-// j0: added to the block residue; a wave that only ever fetches blocks with
-// blk % 4 == w passes j0 = w and uses voff[0].
-__device__ inline void dma_lane_init(DmaLane &d, int64_t stride, int lane, int j0 = 0) {
+__device__ inline void dma_lane_init(DmaLane &d, int64_t stride, int lane) {
   const unsigned rl = lane >> 4, cpos = lane & 15, row_bytes = (unsigned)stride * 2u;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) d.voff[j] = rl * row_bytes + (((cpos ^ (rl << 2)) ^ ((j + j0) & 3)) << 4);
+  for (int j = 0; j < 4; ++j) d.voff[j] = rl * row_bytes + (((cpos ^ (rl << 2)) ^ j) << 4);
 }
 
 // Fetch ROWS rows into the tile at `tile` (LDS).  NW waves cooperate: wave w
-// issues blocks w, w + NW, ...  CONTIG: rows are keys kbase + r; rows outside
+// issues blocks w ROWS/4/NW, ... (consecutive).  CONTIG: rows are keys kbase + r; rows outside
 // [0, N) are clamped (the caller masks them); a step that lies wholly inside
 // [0, N) -- the common case -- takes the uniform-base form, which costs scalar
 // ALU work only.  Otherwise keys come from cols[r] in LDS (KEY_NONE reads row 0
@@ -120,9 +118,8 @@ __device__ inline void dma_rows(const bf16_t *g, int64_t stride, const DmaLane &
     const bf16_t *ubase = g + (int64_t)kbase * stride;
 #pragma unroll
     for (int i = 0; i < ROWS / 4 / NW; ++i) {
-      const int blk = wave + NW * i;
-      // NW == 4: blk & 3 == wave for every i; NW == 1: blk & 3 == i & 3 (compile time)
-      const unsigned voff = NW == 4 ? dl.voff[0] : dl.voff[i & 3];
+      const int blk = wave * (ROWS / 4 / NW) + i;    // ROWS / 4 / NW is a multiple of 4: blk & 3 == i & 3
+      const unsigned voff = dl.voff[i & 3];
       dma16_su(ubase + (int64_t)(4 * blk) * stride, voff, base + blk * 1024);
     }
     return;
@@ -130,7 +127,7 @@ __device__ inline void dma_rows(const bf16_t *g, int64_t stride, const DmaLane &
   const int rl = lane >> 4, cpos = lane & 15;
 #pragma unroll
   for (int i = 0; i < ROWS / 4 / NW; ++i) {
-    const int blk = wave + NW * i;
+    const int blk = wave * (ROWS / 4 / NW) + i;
     const int r = 4 * blk + rl;
     const int c = cpos ^ swz_f(r);
     int key;
