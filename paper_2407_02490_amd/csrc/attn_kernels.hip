@@ -994,34 +994,92 @@ struct Step {
   const int *cols;
 };
 
-// Software-pipelined optimistic pass over the steps a generator yields (skipped
-// steps are never yielded).  At the top of iteration t the loads of K(t+2) and
-// V(t+1) are issued; then QK(t+1) runs fused with the softmax of step t, then
-// P V of step t.  K(t+2) lands in the buffer QK(t) has finished with.
-template <class Gen, bool GATHER>
+// Two loads of one round of the single-wave pipeline: blocks B and B + 1 of the
+// eight 1 KiB blocks of a 32-row step, both with the M0 value set here.
+// ROWS256 (rows 256 bytes apart in global memory, as in LDS): blocks 0..3 hang off
+// base and M0 through the immediate offset, blocks 4..7 off base + 4096.
+template <bool ROWS256, int B>
+__device__ inline void dma_pair(const char *step_row0, unsigned rb, const unsigned (&voff)[4], unsigned lds_step) {
+  if (ROWS256) {
+    const char *base = step_row0 + (B >= 4 ? 4096 : 0);
+    const unsigned m = lds_step + (B >= 4 ? 4096 : 0);
+    if ((B & 3) == 0)
+      asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2\n\t"
+                   "global_load_lds_dwordx4 %1, %2 offset:1024"
+                   :: "v"(voff[0]), "v"(voff[1]), "s"(base), "s"(m) : "memory");
+    else
+      asm volatile("s_mov_b32 m0, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %2 offset:2048\n\t"
+                   "global_load_lds_dwordx4 %1, %2 offset:3072"
+                   :: "v"(voff[2]), "v"(voff[3]), "s"(base), "s"(m) : "memory");
+  } else {
+    dma16_imm<0>(step_row0 + (size_t)(4 * B) * rb, voff[B & 3], lds_step + B * 1024);
+    dma16_imm<0>(step_row0 + (size_t)(4 * B + 4) * rb, voff[(B + 1) & 3], lds_step + (B + 1) * 1024);
+  }
+}
+// Gathered rows: lane L of block blk fetches chunk c of row cols[4 blk + L / 16];
+// the byte offset key * rb + 16 c fits 32 bits (checked on the host: N rb < 2^32),
+// key < 2^24.  KEY_NONE entries read row 0 (the caller masks them).
+template <int B>
+__device__ inline void dma_pair_gather(const char *head, unsigned rb, const int *cols, unsigned lds_step,
+                                       int lane) {
+  const int rl = lane >> 4, cpos = lane & 15;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int blk = B + j, r = 4 * blk + rl;
+    int key = cols[r];
+    key = key == KEY_NONE ? 0 : key;
+    const unsigned ofs = __umul24((unsigned)key, rb) + (unsigned)((cpos ^ swz_f(r)) << 4);
+    dma16_su(head, ofs, lds_step + blk * 1024);
+  }
+}
+
+// Software-pipelined optimistic pass over the 32-key steps a generator yields
+// (skipped steps are never yielded), one wave, private K/V double buffers.
+// Iteration t: the logits of step t+1 (K Q^T, 16 MFMAs) are formed while the
+// vector ALU turns the logits of step t into P(t); the output update of step t
+// (16 MFMAs) follows its half of P(t) by three rounds.  Logits live in vector
+// registers, Q and the LDS operands in accumulator registers (see mfma_qk_*).
+// The iteration is built to an instruction budget like the shared-tile loop:
+// 8 rounds; per round one batch of LDS reads for the round after and one wait;
+// the 16 tile loads (K of step t+2 into the buffer step t's logits came from,
+// V of step t+1 into the buffer of step t-1) go out two per round; the
+// generator advances between MFMAs.  When the generator runs dry the loads
+// repeat an earlier step into the free buffer and the MFMAs form logits nobody
+// consumes, so that the body stays one straight path.
+template <class Gen, bool GATHER, bool ROWS256>
 struct WavePipe {
   Gen &gen;
   WaveState &st;
+  const QAcc &qa;
   bool &has_ref;
   const LaneOfs &lo;
   StepBuf buf;
-  const bf16_t *kh, *vh;
-  int64_t k_st, v_st;
+  const char *kh, *vh;       // head bases (bytes)
+  unsigned k_rb, v_rb;
+  const DmaLane &dk, &dv;
   int N;
   MaskP mp;
   float c_log2;
   int lane;
   Step d0, d1, d2;
   bool h0, h1, h2;
-  DmaLane dk, dv;
 
-  __device__ inline void fetch_k(const Step &d, int slot) const {
-    if (GATHER) dma_rows<1, 32, false>(kh, k_st, dk, 0, d.cols, N, buf.k(slot), 0, lane);
-    else dma_rows<1, 32, true>(kh, k_st, dk, d.kbase, nullptr, N, buf.k(slot), 0, lane);
+  __device__ inline const char *row0(const char *head, unsigned rb, const Step &d) const {
+    // the generators yield steps inside [0, N), the clamp only guards the fetch; step descriptors
+    // come out of LDS lists, i.e. out of vector registers, although they are wave-uniform
+    const int kb = __builtin_amdgcn_readfirstlane(min(max(d.kbase, 0), N - 32));
+    return head + (size_t)kb * rb;
   }
-  __device__ inline void fetch_v(const Step &d, int slot) const {
-    if (GATHER) dma_rows<1, 32, false>(vh, v_st, dv, 0, d.cols, N, buf.v(slot), 0, lane);
-    else dma_rows<1, 32, true>(vh, v_st, dv, d.kbase, nullptr, N, buf.v(slot), 0, lane);
+  template <int R>
+  __device__ inline void round_dma(const char *kt, const char *vt, const int *kcols, const int *vcols,
+                                   unsigned k_dst, unsigned v_dst) const {
+    if (GATHER) {
+      if ((R & 1) == 0) dma_pair_gather<R>(kh, k_rb, kcols, k_dst, lane);
+      else dma_pair_gather<R - 1>(vh, v_rb, vcols, v_dst, lane);
+    } else {
+      if ((R & 1) == 0) dma_pair<ROWS256, R>(kt, k_rb, dk.voff, k_dst);
+      else dma_pair<ROWS256, R - 1>(vt, v_rb, dv.voff, v_dst);
+    }
   }
   __device__ inline void fresh(f32x16 (&s)[1][2], const Step &d) {
     if (d.cls == 2 || !has_ref) {
@@ -1036,37 +1094,146 @@ struct WavePipe {
     }
     has_ref = true;
   }
-  __device__ inline void iter(int t, f32x16 (&s_cur)[1][2], f32x16 (&s_nxt)[1][2]) {
-    int issued = 0;
-    if (h2) { fetch_k(d2, t & 1); issued += 8; }
-    if (h1) { fetch_v(d1, (t + 1) & 1); issued += 8; }
-    if (issued == 16) MINF_WAIT_VMCNT(16); else MINF_WAIT_VMCNT(0);
-    bf16x8 p[2][1][2];
-    if (h1) {
-      fused_qk_softmax<1>(s_nxt, p, st, s_cur, lo, buf.k((t + 1) & 1), c_log2);
-      fresh(s_nxt, d1);
-    } else {
-      softmax_tile<1>(p, st, s_cur, c_log2);
+  // K Q^T of one step into vector registers (start of the pipeline)
+  __device__ inline void qk_first(f32x16 (&s)[1][2], const char *tK) const {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const bf16x8 a = lds_read_k(tK, lo.k[ks]);
+      if (ks == 0) {
+        mfma_qk_first(s[0][0], a, qa.q[0][0]);
+        mfma_qk_first(s[0][1], a, qa.q[1][0]);
+      } else {
+        mfma_qk_acc(s[0][0], a, qa.q[0][ks]);
+        mfma_qk_acc(s[0][1], a, qa.q[1][ks]);
+      }
     }
-    pv_tile<1>(st, lo, buf.v(t & 1), p);
-    d0 = d1; d1 = d2;
-    h0 = h1; h1 = h2;
-    h2 = h2 && gen.next(d2);
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");   // results readable by the vector ALU
+  }
+
+  __device__ inline void iter(int t, f32x16 (&s_cur)[1][2], f32x16 (&s_nxt)[1][2]) {
+    MINF_WAIT_VMCNT(0);      // K of step t+1 and V of step t, issued during the previous iteration
+    const char *tK = buf.k((t + 1) & 1), *tV = buf.v(t & 1);
+    const unsigned k_dst = lds_addr_of(buf.k(t & 1)), v_dst = lds_addr_of(buf.v((t + 1) & 1));
+    bf16x8 kf[8], vf[8], p[2][2];
+    kf[0] = lds_read_k(tK, lo.k[0]);
+    const char *kt = row0(kh, k_rb, d2), *vt = row0(vh, v_rb, d1);
+    const int *kcols = d2.cols, *vcols = d1.cols;     // the generator advances mid-iteration
+    const float m0 = st.m[0], m1 = st.m[1];
+    float lsum0 = 0.f, lsum1 = 0.f;
+    auto fetch_v = [&](int i) {            // output update step i = (t, db)
+      const int base = 16 * (i >> 2) * ROW_BYTES, db = i & 3;
+      return lds_read_vt(tV, lo.v[db][0] + base, lo.v[db][1] + base);
+    };
+    // pair e of the 16 logit pairs per lane, walked [t][nb][r]: P group (nb, t) is
+    // complete after pairs 8t + 4nb .. + 3
+    auto softmax2 = [&](int e) {
+      const int tt = e >> 3, nb = (e >> 2) & 1, r = 8 * tt + 2 * (e & 3);
+      const float m_use = nb == 0 ? m0 : m1;
+      const float e0 = fast_exp2(fmaf(s_cur[0][nb][r], c_log2, -m_use));
+      const float e1 = fast_exp2(fmaf(s_cur[0][nb][r + 1], c_log2, -m_use));
+      if (nb == 0) lsum0 += e0 + e1; else lsum1 += e0 + e1;
+      const f32x2 two = {e0, e1};
+      unsigned pk = __builtin_bit_cast(unsigned, __builtin_convertvector(two, bf16x2));
+      asm volatile("" : "+v"(pk), "+v"(lsum0), "+v"(lsum1));
+      const bf16x2 b2 = __builtin_bit_cast(bf16x2, pk);
+      p[nb][tt][2 * (e & 3)] = b2[0];
+      p[nb][tt][2 * (e & 3) + 1] = b2[1];
+    };
+    auto pv_step = [&](int i) {
+      const int tt = i >> 2, db = i & 3;
+      st.o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], p[0][tt], st.o[db][0], 0, 0, 0);
+      st.o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], p[1][tt], st.o[db][1], 0, 0, 0);
+    };
+    // schedule per round: logit pairs [SM0, SM1) and output update steps [PV0, PV1)
+    //  round        0  1  2  3  4  5  6  7
+    //  pairs        3  3  2  3  3  2  -  -      (first half of P complete after round 2, second after 5)
+    //  update steps -  -  -  1  2  1  2  2
+    auto round = [&](auto rc_, auto sm0_, auto sm1_, auto pv0_, auto pv1_) {
+      constexpr int r = decltype(rc_)::value, SM0 = decltype(sm0_)::value, SM1 = decltype(sm1_)::value;
+      constexpr int PV0 = decltype(pv0_)::value, PV1 = decltype(pv1_)::value;
+      // operands of the round after this one; then wait for this round's (issued a round ago)
+      constexpr int NPV_NEXT = r == 2 ? 1 : r == 3 ? 2 : r == 4 ? 1 : (r == 5 || r == 6) ? 2 : 0;
+      constexpr int PV_NEXT0 = PV1;
+      if (r + 1 < 8) kf[(r + 1) & 7] = lds_read_k(tK, lo.k[(r + 1) & 7]);
+#pragma unroll
+      for (int i = 0; i < NPV_NEXT; ++i) vf[(PV_NEXT0 + i) & 7] = fetch_v((PV_NEXT0 + i) & 7);
+      constexpr int NEW = (r + 1 < 8 ? 1 : 0) + 2 * NPV_NEXT;      // LDS reads just issued
+      __builtin_amdgcn_s_waitcnt(0xC07F | (NEW << 8));
+      round_dma<r>(kt, vt, kcols, vcols, k_dst, v_dst);
+      if (r == 0) {
+        mfma_qk_first(s_nxt[0][0], kf[0], qa.q[0][0]);
+        mfma_qk_first(s_nxt[0][1], kf[0], qa.q[1][0]);
+      } else {
+        mfma_qk_acc(s_nxt[0][0], kf[r], qa.q[0][r]);
+        mfma_qk_acc(s_nxt[0][1], kf[r], qa.q[1][r]);
+      }
+#pragma unroll
+      for (int e = SM0; e < SM1; ++e) {
+        softmax2(e);
+        if (e + 1 < SM1 || PV0 == PV1) __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int i = PV0; i < PV1; ++i) {
+        pv_step(i);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if (r == 3) {
+        // advance the generator between MFMAs: the step after d2
+        d0 = d1; d1 = d2;
+        h0 = h1; h1 = h2;
+        Step dn = d2;
+        h2 = h2 && gen.next(dn);
+        if (h2) d2 = dn;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+#define MINF_IC(n) std::integral_constant<int, n>{}
+    round(MINF_IC(0), MINF_IC(0), MINF_IC(3), MINF_IC(0), MINF_IC(0));
+    round(MINF_IC(1), MINF_IC(3), MINF_IC(6), MINF_IC(0), MINF_IC(0));
+    round(MINF_IC(2), MINF_IC(6), MINF_IC(8), MINF_IC(0), MINF_IC(0));
+    round(MINF_IC(3), MINF_IC(8), MINF_IC(11), MINF_IC(0), MINF_IC(1));
+    round(MINF_IC(4), MINF_IC(11), MINF_IC(14), MINF_IC(1), MINF_IC(3));
+    round(MINF_IC(5), MINF_IC(14), MINF_IC(16), MINF_IC(3), MINF_IC(4));
+    round(MINF_IC(6), MINF_IC(16), MINF_IC(16), MINF_IC(4), MINF_IC(6));
+    round(MINF_IC(7), MINF_IC(16), MINF_IC(16), MINF_IC(6), MINF_IC(8));
+#undef MINF_IC
+    st.l[0] += lsum0;
+    st.l[1] += lsum1;
+    // after the generator advanced in round 3: d0 = the step whose logits are now in s_nxt
+    if (h0) fresh(s_nxt, d0);
   }
   __device__ inline void run() {
-    dma_lane_init(dk, k_st, lane);
-    dma_lane_init(dv, v_st, lane);
     h0 = gen.next(d0);
-    h1 = h0 && gen.next(d1);
-    h2 = h1 && gen.next(d2);
     if (!h0) return;
-    fetch_k(d0, 0);
-    if (h1) fetch_k(d1, 1);
-    fetch_v(d0, 0);
+    d1 = d0;
+    h1 = gen.next(d1);
+    d2 = d1;
+    h2 = h1 && gen.next(d2);
+    const unsigned k0 = lds_addr_of(buf.k(0)), k1 = lds_addr_of(buf.k(1)), v0 = lds_addr_of(buf.v(0));
+    {
+      const char *a = row0(kh, k_rb, d0), *b = row0(kh, k_rb, d1), *c = row0(vh, v_rb, d0);
+      // K of steps 0 and 1, V of step 0
+      if (GATHER) {
+        dma_pair_gather<0>(kh, k_rb, d0.cols, k0, lane); dma_pair_gather<2>(kh, k_rb, d0.cols, k0, lane);
+        dma_pair_gather<4>(kh, k_rb, d0.cols, k0, lane); dma_pair_gather<6>(kh, k_rb, d0.cols, k0, lane);
+        dma_pair_gather<0>(kh, k_rb, d1.cols, k1, lane); dma_pair_gather<2>(kh, k_rb, d1.cols, k1, lane);
+        dma_pair_gather<4>(kh, k_rb, d1.cols, k1, lane); dma_pair_gather<6>(kh, k_rb, d1.cols, k1, lane);
+        dma_pair_gather<0>(vh, v_rb, d0.cols, v0, lane); dma_pair_gather<2>(vh, v_rb, d0.cols, v0, lane);
+        dma_pair_gather<4>(vh, v_rb, d0.cols, v0, lane); dma_pair_gather<6>(vh, v_rb, d0.cols, v0, lane);
+      } else {
+        dma_pair<ROWS256, 0>(a, k_rb, dk.voff, k0); dma_pair<ROWS256, 2>(a, k_rb, dk.voff, k0);
+        dma_pair<ROWS256, 4>(a, k_rb, dk.voff, k0); dma_pair<ROWS256, 6>(a, k_rb, dk.voff, k0);
+        dma_pair<ROWS256, 0>(b, k_rb, dk.voff, k1); dma_pair<ROWS256, 2>(b, k_rb, dk.voff, k1);
+        dma_pair<ROWS256, 4>(b, k_rb, dk.voff, k1); dma_pair<ROWS256, 6>(b, k_rb, dk.voff, k1);
+        dma_pair<ROWS256, 0>(c, v_rb, dv.voff, v0); dma_pair<ROWS256, 2>(c, v_rb, dv.voff, v0);
+        dma_pair<ROWS256, 4>(c, v_rb, dv.voff, v0); dma_pair<ROWS256, 6>(c, v_rb, dv.voff, v0);
+      }
+    }
     MINF_WAIT_VMCNT(0);
     f32x16 sa[1][2], sb[1][2];
-    qk_tile<1>(sa, st, lo, buf.k(0));
+    qk_first(sa, buf.k(0));
     fresh(sa, d0);
+    // iteration t: d0 = step t (logits in hand), d1 = step t+1 (K landed or landing), d2 = step t+2
     int t = 0;
     while (h0) {
       iter(t, sa, sb);
@@ -1074,6 +1241,7 @@ struct WavePipe {
       iter(t + 1, sb, sa);
       t += 2;
     }
+    MINF_WAIT_VMCNT(0);      // the repeated loads of the last iterations
   }
 };
 
@@ -1146,6 +1314,7 @@ struct BsGen {
   }
 };
 
+template <bool ROWS256>
 __global__ __launch_bounds__(64) void bs_kernel(QKV x, HeadList hl, const int32_t *blk_idx,
                                                 const int32_t *blk_cnt, int topk, Sched sched) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -1175,6 +1344,11 @@ __global__ __launch_bounds__(64) void bs_kernel(QKV x, HeadList hl, const int32_
   int *llist = reinterpret_cast<int *>(lds + 4 * HALF_BYTES);
   c.list = llist;
 
+  QAcc qa;
+  pin_q(qa, st);
+  DmaLane dk, dv;
+  dma_lane_init(dk, x.k_st, lane);
+  dma_lane_init(dv, x.v_st, lane);
   const int total = c.cnt;
   bool has_ref = false;
   for (int r0 = 0; r0 < total; r0 += BS_LIST_CAP) {
@@ -1182,13 +1356,16 @@ __global__ __launch_bounds__(64) void bs_kernel(QKV x, HeadList hl, const int32_
     for (int i = lane; i < c.cnt; i += 64) llist[i] = glist[r0 + i];
     __syncthreads();
     BsGen gen{c, mp, 0, 0};
-    WavePipe<BsGen, false> pipe{gen, st, has_ref, lo, c.buf, c.kh, c.vh, c.k_st, c.v_st, c.N, mp, c.c_log2, lane};
+    WavePipe<BsGen, false, ROWS256> pipe{gen, st, qa, has_ref, lo, c.buf, reinterpret_cast<const char *>(c.kh),
+                                         reinterpret_cast<const char *>(c.vh), (unsigned)x.k_st * 2u,
+                                         (unsigned)x.v_st * 2u, dk, dv, c.N, mp, c.c_log2, lane};
     pipe.run();
     __syncthreads();
   }
   if (needs_exact(st)) {
     c.list = glist;
     c.cnt = total;
+    load_q(st, qh, x.q_st, q0, lane);   // the pipelined pass kept Q in accumulator registers only
     reset_for_max_pass(st);
     bs_pass<PASS_MAX>(c, st, lo, mp, lane);
     finish_max_pass(st, x.c_log2);
@@ -1307,10 +1484,13 @@ struct VsRunGen {
   __device__ inline bool next(Step &d) {
     while (true) {
       if (pos < ke) {
-        d.kbase = pos; d.lo = ks; d.hi = ke; d.cols = nullptr;
+        // the step covers the keys pos .. pos+31 of the run; near the end of the
+        // sequence its 32 fetched rows are shifted back to stay inside [0, N) and
+        // the window's lower bound hides the rows the step before already took
+        d.kbase = min(pos, N - 32); d.lo = pos; d.hi = ke; d.cols = nullptr;
         // the run is causal up to q0 + 63 by construction; only the key window and
         // the diagonal can mask elements
-        d.cls = (pos >= ks && pos + 31 < ke && pos + 31 <= q0) ? 1 : 2;
+        d.cls = (d.kbase == pos && pos + 31 < ke && pos + 31 <= q0) ? 1 : 2;
         pos += 32;
         return true;
       }
@@ -1339,10 +1519,18 @@ struct VsColGen {
 };
 
 // Optimistic pass of the Vertical-Slash kernel, software pipelined.
+template <bool ROWS256>
 __device__ inline void vs_pass_pipelined(const VsCtx &c, WaveState &st, const LaneOfs &lo, const MaskP &mp,
                                          int2 *lruns, int lane) {
   const int q0 = c.q0;
   bool has_ref = false;
+  QAcc qa;
+  pin_q(qa, st);
+  DmaLane dk, dv;
+  dma_lane_init(dk, c.k_st, lane);
+  dma_lane_init(dv, c.v_st, lane);
+  const char *khb = reinterpret_cast<const char *>(c.kh), *vhb = reinterpret_cast<const char *>(c.vh);
+  const unsigned k_rb = (unsigned)c.k_st * 2u, v_rb = (unsigned)c.v_st * 2u;
   // ---- phase A: slash runs, staged VS_RUN_CAP at a time
   for (int r0 = 0; r0 < c.n_c; r0 += VS_RUN_CAP) {
     const int n = min(c.n_c - r0, VS_RUN_CAP);
@@ -1357,7 +1545,7 @@ __device__ inline void vs_pass_pipelined(const VsCtx &c, WaveState &st, const La
     for (int off = 32; off > 0; off >>= 1) usable += __shfl_xor(usable, off);
     __syncthreads();
     VsRunGen gen{lruns, usable, q0, c.N, 0, 0, 0, 0};
-    WavePipe<VsRunGen, false> pipe{gen, st, has_ref, lo, c.buf, c.kh, c.vh, c.k_st, c.v_st, c.N, mp, c.c_log2, lane};
+    WavePipe<VsRunGen, false, ROWS256> pipe{gen, st, qa, has_ref, lo, c.buf, khb, vhb, k_rb, v_rb, dk, dv, c.N, mp, c.c_log2, lane};
     pipe.run();
     __syncthreads();
     if (usable < n) break;
@@ -1388,12 +1576,13 @@ __device__ inline void vs_pass_pipelined(const VsCtx &c, WaveState &st, const La
     if (lane + ncol < nstep * 32) cols[ncol + lane] = KEY_NONE;   // pad the last step
     __syncthreads();
     VsColGen gen{cols, nstep, q0, 0};
-    WavePipe<VsColGen, true> pipe{gen, st, has_ref, lo, c.buf, c.kh, c.vh, c.k_st, c.v_st, c.N, mp, c.c_log2, lane};
+    WavePipe<VsColGen, true, ROWS256> pipe{gen, st, qa, has_ref, lo, c.buf, khb, vhb, k_rb, v_rb, dk, dv, c.N, mp, c.c_log2, lane};
     pipe.run();
     __syncthreads();
   }
 }
 
+template <bool ROWS256>
 __global__ __launch_bounds__(64) void vs_kernel(QKV x, HeadList hl, const int32_t *v_idx,
                                                 const int32_t *cover, const uint32_t *cover_bits,
                                                 const int32_t *counts, int nv, int ns, int cover_words,
@@ -1426,8 +1615,9 @@ __global__ __launch_bounds__(64) void vs_kernel(QKV x, HeadList hl, const int32_
   MaskP mp;
   mp.q0 = q0; mp.n_init = KEY_NONE; mp.n_local = 1; mp.lo = 0; mp.hi = 0;
 
-  vs_pass_pipelined(c, st, lo, mp, reinterpret_cast<int2 *>(c.cols + VCAP + 64), lane);
+  vs_pass_pipelined<ROWS256>(c, st, lo, mp, reinterpret_cast<int2 *>(c.cols + VCAP + 64), lane);
   if (needs_exact(st)) {
+    load_q(st, qh, x.q_st, q0, lane);   // the pipelined pass kept Q in accumulator registers only
     reset_for_max_pass(st);
     vs_pass<PASS_MAX>(c, st, lo, mp, lane);
     finish_max_pass(st, x.c_log2);
@@ -1465,9 +1655,15 @@ hipError_t launch_bs(const QKV &x, const HeadList &hl, const int32_t *blk_idx, c
   const int NB = x.N / BQ;
   const Sched s = make_sched(hl.n, NB);
   const size_t lds = 4 * HALF_BYTES + BS_LIST_CAP * sizeof(int);
-  hipError_t e = set_lds(reinterpret_cast<const void *>(bs_kernel), lds);
+  const bool rows256 = x.k_st == D && x.v_st == D;
+  const void *fn = rows256 ? reinterpret_cast<const void *>(bs_kernel<true>)
+                           : reinterpret_cast<const void *>(bs_kernel<false>);
+  hipError_t e = set_lds(fn, lds);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(bs_kernel, dim3(s.per_xcd * 8), dim3(64), lds, st, x, hl, blk_idx, blk_cnt, topk, s);
+  if (rows256)
+    hipLaunchKernelGGL(bs_kernel<true>, dim3(s.per_xcd * 8), dim3(64), lds, st, x, hl, blk_idx, blk_cnt, topk, s);
+  else
+    hipLaunchKernelGGL(bs_kernel<false>, dim3(s.per_xcd * 8), dim3(64), lds, st, x, hl, blk_idx, blk_cnt, topk, s);
   return hipGetLastError();
 }
 
@@ -1477,10 +1673,20 @@ hipError_t launch_vs(const QKV &x, const HeadList &hl, const int32_t *v_idx, con
   const int NB = x.N / BQ;
   const Sched s = make_sched(hl.n, NB);
   const size_t lds = 4 * HALF_BYTES + (VCAP + 64) * sizeof(int) + VS_RUN_CAP * sizeof(int2);
-  hipError_t e = set_lds(reinterpret_cast<const void *>(vs_kernel), lds);
+  // gathered rows are addressed with 32-bit byte offsets from the head base
+  if ((uint64_t)x.N * (uint64_t)x.k_st * 2u >= (1ull << 32) || (uint64_t)x.N * (uint64_t)x.v_st * 2u >= (1ull << 32))
+    return hipErrorInvalidValue;
+  const bool rows256 = x.k_st == D && x.v_st == D;
+  const void *fn = rows256 ? reinterpret_cast<const void *>(vs_kernel<true>)
+                           : reinterpret_cast<const void *>(vs_kernel<false>);
+  hipError_t e = set_lds(fn, lds);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(vs_kernel, dim3(s.per_xcd * 8), dim3(64), lds, st, x, hl, v_idx, cover, cover_bits,
-                     counts, nv, ns, cover_words, s);
+  if (rows256)
+    hipLaunchKernelGGL(vs_kernel<true>, dim3(s.per_xcd * 8), dim3(64), lds, st, x, hl, v_idx, cover, cover_bits,
+                       counts, nv, ns, cover_words, s);
+  else
+    hipLaunchKernelGGL(vs_kernel<false>, dim3(s.per_xcd * 8), dim3(64), lds, st, x, hl, v_idx, cover, cover_bits,
+                       counts, nv, ns, cover_words, s);
   return hipGetLastError();
 }
 
