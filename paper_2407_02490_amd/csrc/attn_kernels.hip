@@ -46,8 +46,6 @@ namespace minf {
 constexpr int BS_LIST_CAP = 512;          // block ids staged in LDS per round of the Block-Sparse walk
 constexpr int VS_RUN_CAP = 256;           // slash runs staged in LDS per round of the Vertical-Slash walk
 constexpr int VCAP = 1024;               // compacted vertical columns held in LDS per round
-constexpr int TILE_BYTES = 64 * ROW_BYTES;   // 64 rows of K or of V
-constexpr int HALF_BYTES = 32 * ROW_BYTES;   // 32 rows
 constexpr float L_LIMIT = 1.2676506e30f;  // 2^100: beyond it the optimistic pass is redone exactly
 
 struct WaveState {
@@ -66,7 +64,6 @@ struct MaskP {
   int n_init, n_local;
 };
 
-#define MINF_WAIT_VMCNT(n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory")
 
 // ---- per-wave setup / epilogue ---------------------------------------------
 __device__ inline void set_reference(WaveState &st, int nb, float m) { st.m[nb] = m; }
@@ -1042,7 +1039,8 @@ __device__ inline void dma_pair_gather(const char *head, unsigned rb, const int 
 // The iteration is built to an instruction budget like the shared-tile loop:
 // 8 rounds; per round one batch of LDS reads for the round after and one wait;
 // the 16 tile loads (K of step t+2 into the buffer step t's logits came from,
-// V of step t+1 into the buffer of step t-1) go out two per round; the
+// V of step t+1 into the buffer of step t-1) go out two per round, K first: K
+// must have landed at the top of the next iteration, V only by its round 2; the
 // generator advances between MFMAs.  When the generator runs dry the loads
 // repeat an earlier step into the free buffer and the MFMAs form logits nobody
 // consumes, so that the body stays one straight path.
@@ -1073,12 +1071,14 @@ struct WavePipe {
   template <int R>
   __device__ inline void round_dma(const char *kt, const char *vt, const int *kcols, const int *vcols,
                                    unsigned k_dst, unsigned v_dst) const {
+    // K in rounds 0..3, V in rounds 4..7: K is needed at the top of the next iteration, V not
+    // before its round 2
     if (GATHER) {
-      if ((R & 1) == 0) dma_pair_gather<R>(kh, k_rb, kcols, k_dst, lane);
-      else dma_pair_gather<R - 1>(vh, v_rb, vcols, v_dst, lane);
+      if (R < 4) dma_pair_gather<2 * (R & 3)>(kh, k_rb, kcols, k_dst, lane);
+      else dma_pair_gather<2 * (R & 3)>(vh, v_rb, vcols, v_dst, lane);
     } else {
-      if ((R & 1) == 0) dma_pair<ROWS256, R>(kt, k_rb, dk.voff, k_dst);
-      else dma_pair<ROWS256, R - 1>(vt, v_rb, dv.voff, v_dst);
+      if (R < 4) dma_pair<ROWS256, 2 * (R & 3)>(kt, k_rb, dk.voff, k_dst);
+      else dma_pair<ROWS256, 2 * (R & 3)>(vt, v_rb, dv.voff, v_dst);
     }
   }
   __device__ inline void fresh(f32x16 (&s)[1][2], const Step &d) {
@@ -1111,7 +1111,7 @@ struct WavePipe {
   }
 
   __device__ inline void iter(int t, f32x16 (&s_cur)[1][2], f32x16 (&s_nxt)[1][2]) {
-    MINF_WAIT_VMCNT(0);      // K of step t+1 and V of step t, issued during the previous iteration
+    MINF_WAIT_VMCNT(8);      // K of step t+1 has landed (V of step t, issued after it, may be in flight)
     const char *tK = buf.k((t + 1) & 1), *tV = buf.v(t & 1);
     const unsigned k_dst = lds_addr_of(buf.k(t & 1)), v_dst = lds_addr_of(buf.v((t + 1) & 1));
     bf16x8 kf[8], vf[8], p[2][2];
@@ -1160,6 +1160,7 @@ struct WavePipe {
       constexpr int NEW = (r + 1 < 8 ? 1 : 0) + 2 * NPV_NEXT;      // LDS reads just issued
       __builtin_amdgcn_s_waitcnt(0xC07F | (NEW << 8));
       round_dma<r>(kt, vt, kcols, vcols, k_dst, v_dst);
+      if (r == 1) MINF_WAIT_VMCNT(4);      // V of step t has landed: round 2 starts reading it
       if (r == 0) {
         mfma_qk_first(s_nxt[0][0], kf[0], qa.q[0][0]);
         mfma_qk_first(s_nxt[0][1], kf[0], qa.q[1][0]);

@@ -22,7 +22,6 @@ namespace minf {
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 
 constexpr int VS_CHUNK = 1024;      // keys / offsets owned by one workgroup of the score kernels
-constexpr int P_PITCH = 68;         // floats per LDS row of the probability tile
 
 struct KvMap {                      // pooling work list of the Block-Sparse build
   int32_t n_kv;                     // distinct KV heads used by the call
@@ -150,67 +149,46 @@ __device__ inline void ordered_select(const float *data, int n, unsigned thr, in
 }
 
 // ---------------------------------------------------------------------------
-// K tile staging for the estimate (K only, one wave)
-// ---------------------------------------------------------------------------
-struct KRegs { uint4 k[16]; };
-
-__device__ inline void ktile_issue(KRegs &r, const bf16_t *kh, int64_t k_st, int kbase, int lane) {
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const int c = lane + 64 * i, row = c >> 4, col = c & 15;
-    r.k[i] = *reinterpret_cast<const uint4 *>(kh + (int64_t)(kbase + row) * k_st + col * 8);
-  }
-}
-__device__ inline void ktile_store(const KRegs &r, bf16_t *ldsK, int lane) {
-#pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const int c = lane + 64 * i, row = c >> 4, col = c & 15;
-    *reinterpret_cast<uint4 *>(ldsK + row * K_PITCH + col * 8) = r.k[i];
-  }
-}
-
-// S^T = K Q^T for one 64-key tile; register r of s[mb][nb] holds key index
-// 32mb + 16(r/8) + 8h + (r%8) and estimating row 32nb + n (n = lane%32, h = lane/32).
-__device__ inline void logits_tile(f32x16 (&s)[2][2], const bf16x8 (&q)[2][8], const bf16_t *ldsK, int lane) {
-  const int n = lane & 31, h = lane >> 5, prow = perm_row(n);
-#pragma unroll
-  for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[mb][nb][r] = 0.f;
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks)
-#pragma unroll
-    for (int mb = 0; mb < 2; ++mb) {
-      bf16x8 a = *reinterpret_cast<const bf16x8 *>(ldsK + (32 * mb + prow) * K_PITCH + 16 * ks + 8 * h);
-      s[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[0][ks], s[mb][0], 0, 0, 0);
-      s[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[1][ks], s[mb][1], 0, 0, 0);
-    }
-}
-
-// ---------------------------------------------------------------------------
 // Vertical-Slash score kernels.  Estimating row r (0..63) is query N-64+r; rows
-// r < 64 - last_q do not take part.  Workgroup (head slot, chunk c) owns the
-// offsets [cC, cC+C) and the keys [N-cC-C, N-cC): tile m of the chunk holds the
-// keys [N-cC-64(m+1), N-cC-64m); offsets of the chunk meet only tiles 0..C/64.
+// r < 64 - last_q do not take part.  Workgroup (head slot, chunk c), one wave,
+// owns the offsets [cC, cC+C) and the keys [N-cC-C, N-cC): tile m of the chunk
+// holds the keys [N-cC-64(m+1), N-cC-64m); offsets of the chunk meet only tiles
+// 0..C/64.  K tiles arrive by direct global -> LDS loads into two buffers (the
+// swizzled layout of the attention kernels), the next tile in flight while the
+// current one is reduced.
+//  pass 1: S^T = K Q^T (keys along the accumulator registers): running row max
+//          and row sum stay inside a lane.
+//  pass 2: S = Q K^T (keys along the lanes, estimating rows along the
+//          registers): a column sum is 32 in-lane adds and one exchange between
+//          the lane halves; every probability is also added to the sum of its
+//          diagonal with an LDS float atomic (one wave, program order: the sums
+//          are reproducible), whose address is one per-lane base per tile plus
+//          an immediate per register.  The 64 x N estimate is never stored.
 // ---------------------------------------------------------------------------
+constexpr int VS_TILE_BYTES = TILE_BYTES;          // 16 KiB
+constexpr int VS_DPAD = 64;                       // slack on both sides of the chunk's diagonal sums
+
+__device__ inline void lds_fadd(float *p, float v) {
+  __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
 template <int PASS>
 __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int last_q, int n_chunks,
                                                       float *ml_part, const float *ml_fin,
                                                       float *colsum, float *diagsum) {
-  extern __shared__ __attribute__((aligned(16))) bf16_t lds[];
-  bf16_t *ldsK = lds;
-  float *P = reinterpret_cast<float *>(lds + K_TILE);          // [64][P_PITCH]
-  float *dacc = P + 64 * P_PITCH;                               // [VS_CHUNK]
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  float *dacc = reinterpret_cast<float *>(lds + 2 * VS_TILE_BYTES);   // [VS_DPAD + VS_CHUNK + VS_DPAD], pass 2
 
   const int slot = blockIdx.y, chunk = blockIdx.x;
-  const int head = hl.h[slot], kvh = head / x.group;
+  const int head = __builtin_amdgcn_readfirstlane(hl.h[slot]);
+  const int kvh = to_sgpr(head / x.group);
   const bf16_t *qh = x.q + head * x.q_sh, *kh = x.k + kvh * x.k_sh;
   const int lane = threadIdx.x, n = lane & 31, h = lane >> 5;
   const int N = x.N, C = VS_CHUNK;
   const int r_min = 64 - last_q;
 
+  // Q fragments: lane (n, h) holds Q[N-64 + 32 nb + n][16 ks + 8 h .. +7], which is the B operand
+  // of K Q^T and the A operand of Q K^T alike
   bf16x8 q[2][8];
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb) {
@@ -218,33 +196,66 @@ __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int la
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) q[nb][ks] = *reinterpret_cast<const bf16x8 *>(row + 16 * ks);
   }
+  LaneOfs lo;
+  lane_offsets(lo, lane);
+  DmaLane dl;
+  dma_lane_init(dl, x.k_st, lane);
 
-  float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
-  float m_fin[2] = {0.f, 0.f}, inv_l[2] = {0.f, 0.f};
+  // pass 1 state: lane (n, h) follows rows 32 nb + n over its half of the keys
+  float m_run0 = -INFINITY, m_run1 = -INFINITY, l_run0 = 0.f, l_run1 = 0.f;
+  // pass 2: per register of the S layout, row 32 nb + 8 (r / 4) + 4 h + r % 4 needs its
+  // exponent offset  max + log2(sum)  (+inf for a row that does not take part: P = 0)
+  float off[2][16];
   if (PASS == 2) {
-    for (int nb = 0; nb < 2; ++nb) {
-      m_fin[nb] = ml_fin[(slot * 64 + 32 * nb + n) * 2 + 0];
-      inv_l[nb] = ml_fin[(slot * 64 + 32 * nb + n) * 2 + 1];
-    }
-    for (int i = lane; i < C; i += 64) dacc[i] = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = 32 * nb + 8 * (r >> 2) + 4 * h + (r & 3);
+        const float mx = ml_fin[(slot * 64 + row) * 2 + 0], inv = ml_fin[(slot * 64 + row) * 2 + 1];
+        off[nb][r] = (row >= r_min && inv > 0.f) ? mx - __builtin_amdgcn_logf(inv) : INFINITY;
+      }
+    for (int i = lane; i < C + 2 * VS_DPAD; i += 64) dacc[i] = 0.f;
+    __syncthreads();
   }
 
   const int key_hi = N - chunk * C;                 // exclusive end of the owned keys
-  const int n_tiles = PASS == 1 ? C / 64 : C / 64 + 1;
-  KRegs regs;
-  int m = 0;
+  const int n_tiles_max = PASS == 1 ? C / 64 : C / 64 + 1;
+  // tiles are 64-aligned: wholly inside [0, N) or outside
+  const int n_tiles = min(n_tiles_max, key_hi / 64);
   auto tile_key = [&](int mm) { return key_hi - 64 * (mm + 1); };
-  if (tile_key(0) >= 0) ktile_issue(regs, kh, x.k_st, tile_key(0), lane);
-  for (; m < n_tiles; ++m) {
+  auto fetch = [&](int mm) {
+    dma_rows<1, 64, true>(kh, x.k_st, dl, tile_key(mm), nullptr, N, lds + (mm & 1) * VS_TILE_BYTES, 0, lane);
+  };
+  if (n_tiles > 0) fetch(0);
+  for (int m = 0; m < n_tiles; ++m) {
     const int kt = tile_key(m);
-    if (kt < 0) break;                               // tiles are 64-aligned: wholly inside or outside
-    ktile_store(regs, ldsK, lane);
-    __syncthreads();
-    if (m + 1 < n_tiles && tile_key(m + 1) >= 0) ktile_issue(regs, kh, x.k_st, tile_key(m + 1), lane);
+    const char *tK = lds + (m & 1) * VS_TILE_BYTES;
+    if (m + 1 < n_tiles) {
+      fetch(m + 1);
+      MINF_WAIT_VMCNT(16);
+    } else {
+      MINF_WAIT_VMCNT(0);
+    }
+    const bool diag_tile = kt + 63 > N - 64;       // only the last 64 keys are cut by causality
     f32x16 s[2][2];
-    logits_tile(s, q, ldsK, lane);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[i][j][r] = 0.f;
 
     if (PASS == 1) {
+      // s[mb][nb]: register e holds key kt + 32 mb + 16 (e / 8) + 8 h + e % 8, row 32 nb + n
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+          const bf16x8 a = lds_read_k(tK, lo.k[ks] + mb * HALF_BYTES);
+          s[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[0][ks], s[mb][0], 0, 0, 0);
+          s[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, q[1][ks], s[mb][1], 0, 0, 0);
+        }
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
         const int r = 32 * nb + n, p = N - 64 + r;
@@ -253,79 +264,78 @@ __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int la
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
-            const int key = kt + 32 * mb + 16 * (e >> 3) + 8 * h + (e & 7);
-            const bool ok = key <= p && r >= r_min;
-            const float v = ok ? s[mb][nb][e] * x.c_log2 : -INFINITY;
+            float v = s[mb][nb][e] * x.c_log2;
+            if (diag_tile) {
+              const int key = kt + 32 * mb + 16 * (e >> 3) + 8 * h + (e & 7);
+              v = key <= p ? v : -INFINITY;
+            }
+            v = r >= r_min ? v : -INFINITY;
             s[mb][nb][e] = v;
             mx = fmaxf(mx, v);
           }
-        const float m_new = fmaxf(m_run[nb], mx);
+        float &m_run = nb == 0 ? m_run0 : m_run1;
+        float &l_run = nb == 0 ? l_run0 : l_run1;
+        const float m_new = fmaxf(m_run, mx);
         const float m_use = m_new == -INFINITY ? 0.f : m_new;
         float sum = 0.f;
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
           for (int e = 0; e < 16; ++e) sum += fast_exp2(s[mb][nb][e] - m_use);
-        l_run[nb] = l_run[nb] * fast_exp2(m_run[nb] - m_use) + sum;
-        m_run[nb] = m_new;
+        l_run = l_run * fast_exp2(m_run - m_use) + sum;
+        m_run = m_new;
       }
     } else {
-      // probabilities -> LDS tile P[row][key index]
+      // s[nb][cb]: register r holds row 32 nb + 8 (r / 4) + 4 h + r % 4, key kt + 32 cb + perm_row(n)
 #pragma unroll
-      for (int nb = 0; nb < 2; ++nb) {
-        const int r = 32 * nb + n, p = N - 64 + r;
+      for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-          for (int t = 0; t < 2; ++t) {
-            float pv[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-              const int key = kt + 32 * mb + 16 * t + 8 * h + i;
-              const bool ok = key <= p && r >= r_min;
-              pv[i] = ok ? fast_exp2(fmaf(s[mb][nb][8 * t + i], x.c_log2, -m_fin[nb])) * inv_l[nb] : 0.f;
-            }
-            float *dst = P + r * P_PITCH + 32 * mb + 16 * t + 8 * h;
-            *reinterpret_cast<f32x4v *>(dst) = (f32x4v){pv[0], pv[1], pv[2], pv[3]};
-            *reinterpret_cast<f32x4v *>(dst + 4) = (f32x4v){pv[4], pv[5], pv[6], pv[7]};
-          }
-      }
-      __syncthreads();
-      // column sums of the owned keys (tiles 0 .. C/64-1): lane = key index
-      if (m < C / 64) {
-        float cs = 0.f;
-#pragma unroll 8
-        for (int r = 0; r < 64; ++r) cs += P[r * P_PITCH + lane];
-        colsum[(int64_t)slot * N + kt + lane] = cs;
-      }
-      // diagonal sums: element (r, key index c) lies on local offset 64m + r - c.
-      // lane handles delta = r - c in {lane - 63, lane + 1}.
-#pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        const int delta = half == 0 ? lane - 63 : lane + 1;
-        float ds = 0.f;
-#pragma unroll 8
-        for (int r = 0; r < 64; ++r) {
-          const int c = r - delta;
-          if (c >= 0 && c < 64) ds += P[r * P_PITCH + c];
+        for (int cb = 0; cb < 2; ++cb) {
+          const bf16x8 kf = lds_read_k(tK, lo.k[ks] + cb * HALF_BYTES);
+          s[0][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[0][ks], kf, s[0][cb], 0, 0, 0);
+          s[1][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[1][ks], kf, s[1][cb], 0, 0, 0);
         }
-        const int local = 64 * m + delta;
-        if (local >= 0 && local < C) dacc[local] += ds;
+      const int kcol = perm_row(n);
+      // diagonal of element (row, key): local offset 64 m + row - (32 cb + kcol); this lane's
+      // part of the address, the rest is known at compile time
+      float *dlane = dacc + VS_DPAD + 64 * m - kcol + 4 * h;
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) {
+        float cs = 0.f;
+#pragma unroll
+        for (int nb = 0; nb < 2; ++nb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int row4 = 32 * nb + 8 * (r >> 2) + (r & 3);       // row - 4 h
+            float pv = fast_exp2(fmaf(s[nb][cb][r], x.c_log2, -off[nb][r]));
+            if (diag_tile) {
+              const int key = kt + 32 * cb + kcol;
+              pv = key <= N - 64 + row4 + 4 * h ? pv : 0.f;
+            }
+            cs += pv;
+            lds_fadd(dlane + row4 - 32 * cb, pv);
+          }
+        // the two lane halves hold the two halves of the rows of the same keys
+        const float other = __shfl_xor(cs, 32);
+        const float tot = h == 0 ? cs + other : other + cs;           // same operand order in both
+        if (h == 0 && m < C / 64) colsum[(int64_t)slot * N + kt + 32 * cb + kcol] = tot;
       }
     }
-    __syncthreads();
+    // the LDS reads of this tile are complete (their data was consumed) before the tile
+    // after next overwrites the buffer: that fetch is issued in the next iteration
   }
 
   if (PASS == 1) {
     // merge the two lanes that share an estimating row, store the chunk's (max, sum)
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
-      const float mo = __shfl_xor(m_run[nb], 32), lo = __shfl_xor(l_run[nb], 32);
-      const float M = fmaxf(m_run[nb], mo);
+      const float m_run = nb == 0 ? m_run0 : m_run1, l_run = nb == 0 ? l_run0 : l_run1;
+      const float mo = __shfl_xor(m_run, 32), lo2 = __shfl_xor(l_run, 32);
+      const float M = fmaxf(m_run, mo);
       const float Mu = M == -INFINITY ? 0.f : M;
       // same operand order in both lanes of the pair: lane-half 0's share first
-      const float a = h == 0 ? l_run[nb] * fast_exp2(m_run[nb] - Mu) : lo * fast_exp2(mo - Mu);
-      const float b = h == 0 ? lo * fast_exp2(mo - Mu) : l_run[nb] * fast_exp2(m_run[nb] - Mu);
+      const float a = h == 0 ? l_run * fast_exp2(m_run - Mu) : lo2 * fast_exp2(mo - Mu);
+      const float b = h == 0 ? lo2 * fast_exp2(mo - Mu) : l_run * fast_exp2(m_run - Mu);
       if (h == 0) {
         float *dst = ml_part + (((int64_t)slot * n_chunks + chunk) * 64 + 32 * nb + n) * 2;
         dst[0] = M;
@@ -333,9 +343,10 @@ __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int la
       }
     }
   } else {
+    __syncthreads();
     for (int i = lane; i < C; i += 64) {
       const int o = chunk * C + i;
-      if (o < N) diagsum[(int64_t)slot * N + o] = dacc[i];
+      if (o < N) diagsum[(int64_t)slot * N + o] = dacc[VS_DPAD + i];
     }
   }
 }
@@ -569,7 +580,7 @@ hipError_t launch_build_vs(const QKV &x, const HeadList &hl, int last_q, int nv,
   float *diagsum = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * N * sizeof(float));
   float *ml_part = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * nc * 128 * sizeof(float));
   float *ml_fin = reinterpret_cast<float *>(p);
-  const size_t lds = K_TILE * sizeof(bf16_t) + (64 * P_PITCH + VS_CHUNK) * sizeof(float);
+  const size_t lds = 2 * VS_TILE_BYTES + (VS_CHUNK + 2 * VS_DPAD) * sizeof(float);
   hipError_t e;
   e = hipFuncSetAttribute(reinterpret_cast<const void *>(vs_score_kernel<1>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

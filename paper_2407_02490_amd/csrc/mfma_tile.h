@@ -19,10 +19,12 @@ constexpr int BQ = 64;         // query rows per wave (one paper block)
 constexpr int BK = 64;         // keys per tile
 constexpr int ROW_BYTES = 256; // one K or V row in LDS (128 bf16)
 constexpr int KEY_NONE = 0x7fffffff;   // gathered column that must not be attended
+constexpr int TILE_BYTES = BK * ROW_BYTES;       // one 64-row K or V tile in LDS
+constexpr int HALF_BYTES = TILE_BYTES / 2;       // 32 rows
 
-// padded row-major K tile used by the Vertical-Slash estimate kernels
-constexpr int K_PITCH = 136;
-constexpr int K_TILE = BK * K_PITCH;
+// Completion of direct global -> LDS loads is awaited by hand (they are issued from
+// inline assembly, the compiler does not track them).
+#define MINF_WAIT_VMCNT(n) asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory")
 
 #define MINF_GPTR(p) ((__attribute__((address_space(1))) void *)(p))
 #define MINF_LPTR(p) ((__attribute__((address_space(3))) void *)(p))
