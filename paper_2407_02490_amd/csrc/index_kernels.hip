@@ -160,17 +160,17 @@ __device__ inline void ordered_select(const float *data, int n, unsigned thr, in
 //          and row sum stay inside a lane.
 //  pass 2: S = Q K^T (keys along the lanes, estimating rows along the
 //          registers): a column sum is 32 in-lane adds and one exchange between
-//          the lane halves; every probability is also added to the sum of its
-//          diagonal with an LDS float atomic (one wave, program order: the sums
-//          are reproducible), whose address is one per-lane base per tile plus
-//          an immediate per register.  The 64 x N estimate is never stored.
+//          the lane halves.  For the diagonal sums the probabilities of 32 rows
+//          go to LDS skewed, element (row, key) at column key - row + 32, so
+//          that a diagonal is a column: every lane then adds up two columns.
+//          Positions the skew never writes hold zeros from the start, so no
+//          bounds are tested.  (LDS float atomics were tried for this and cost
+//          about 700 cycles per instruction.)  One wave, program order: the
+//          sums are reproducible.  The 64 x N estimate is never stored.
 // ---------------------------------------------------------------------------
 constexpr int VS_TILE_BYTES = TILE_BYTES;          // 16 KiB
-constexpr int VS_DPAD = 64;                       // slack on both sides of the chunk's diagonal sums
-
-__device__ inline void lds_fadd(float *p, float v) {
-  __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-}
+constexpr int VS_DPAD = 96;                       // slack on both sides of the chunk's diagonal sums
+constexpr int VS_SKEW_PITCH = 128;                // floats per row of the skewed probability tile (32 rows)
 
 template <int PASS>
 __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int last_q, int n_chunks,
@@ -178,6 +178,7 @@ __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int la
                                                       float *colsum, float *diagsum) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   float *dacc = reinterpret_cast<float *>(lds + 2 * VS_TILE_BYTES);   // [VS_DPAD + VS_CHUNK + VS_DPAD], pass 2
+  float *skew = dacc + VS_CHUNK + 2 * VS_DPAD;                         // [32][VS_SKEW_PITCH], pass 2
 
   const int slot = blockIdx.y, chunk = blockIdx.x;
   const int head = __builtin_amdgcn_readfirstlane(hl.h[slot]);
@@ -215,7 +216,7 @@ __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int la
         const float mx = ml_fin[(slot * 64 + row) * 2 + 0], inv = ml_fin[(slot * 64 + row) * 2 + 1];
         off[nb][r] = (row >= r_min && inv > 0.f) ? mx - __builtin_amdgcn_logf(inv) : INFINITY;
       }
-    for (int i = lane; i < C + 2 * VS_DPAD; i += 64) dacc[i] = 0.f;
+    for (int i = lane; i < C + 2 * VS_DPAD + 32 * VS_SKEW_PITCH; i += 64) dacc[i] = 0.f;   // dacc and skew
     __syncthreads();
   }
 
@@ -296,28 +297,41 @@ __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int la
           s[1][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[1][ks], kf, s[1][cb], 0, 0, 0);
         }
       const int kcol = perm_row(n);
-      // diagonal of element (row, key): local offset 64 m + row - (32 cb + kcol); this lane's
-      // part of the address, the rest is known at compile time
-      float *dlane = dacc + VS_DPAD + 64 * m - kcol + 4 * h;
+      float cs[2] = {0.f, 0.f};
 #pragma unroll
-      for (int cb = 0; cb < 2; ++cb) {
-        float cs = 0.f;
+      for (int nb = 0; nb < 2; ++nb) {
+        // rows 32 nb .. 32 nb + 31: local row rl = 8 (r / 4) + 4 h + r % 4, key column kc = 32 cb + kcol;
+        // element (rl, kc) goes to skew[rl][kc - rl + 32]
+        float *wlane = skew + 4 * h * (VS_SKEW_PITCH - 1) + kcol + 32;
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
+        for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const int row4 = 32 * nb + 8 * (r >> 2) + (r & 3);       // row - 4 h
+            const int rl4 = 8 * (r >> 2) + (r & 3);                    // rl - 4 h
             float pv = fast_exp2(fmaf(s[nb][cb][r], x.c_log2, -off[nb][r]));
             if (diag_tile) {
               const int key = kt + 32 * cb + kcol;
-              pv = key <= N - 64 + row4 + 4 * h ? pv : 0.f;
+              pv = key <= N - 64 + 32 * nb + rl4 + 4 * h ? pv : 0.f;
             }
-            cs += pv;
-            lds_fadd(dlane + row4 - 32 * cb, pv);
+            cs[cb] += pv;
+            wlane[rl4 * (VS_SKEW_PITCH - 1) + 32 * cb] = pv;
           }
+        // column j of the skewed tile is the diagonal with local offset 64 m + 32 nb + 32 - j
+        float t1 = 0.f, t2 = 0.f;
+#pragma unroll 8
+        for (int rl = 0; rl < 32; ++rl) {
+          t1 += skew[rl * VS_SKEW_PITCH + lane];
+          t2 += skew[rl * VS_SKEW_PITCH + 64 + lane];
+        }
+        float *d1 = dacc + VS_DPAD + 64 * m + 32 * nb + 32 - lane;
+        d1[0] += t1;
+        if (lane < 32) d1[-64] += t2;        // columns 96 .. 127 hold no diagonal
+      }
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) {
         // the two lane halves hold the two halves of the rows of the same keys
-        const float other = __shfl_xor(cs, 32);
-        const float tot = h == 0 ? cs + other : other + cs;           // same operand order in both
+        const float other = __shfl_xor(cs[cb], 32);
+        const float tot = h == 0 ? cs[cb] + other : other + cs[cb];   // same operand order in both
         if (h == 0 && m < C / 64) colsum[(int64_t)slot * N + kt + 32 * cb + kcol] = tot;
       }
     }
@@ -580,7 +594,7 @@ hipError_t launch_build_vs(const QKV &x, const HeadList &hl, int last_q, int nv,
   float *diagsum = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * N * sizeof(float));
   float *ml_part = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * nc * 128 * sizeof(float));
   float *ml_fin = reinterpret_cast<float *>(p);
-  const size_t lds = 2 * VS_TILE_BYTES + (VS_CHUNK + 2 * VS_DPAD) * sizeof(float);
+  const size_t lds = 2 * VS_TILE_BYTES + (VS_CHUNK + 2 * VS_DPAD + 32 * VS_SKEW_PITCH) * sizeof(float);
   hipError_t e;
   e = hipFuncSetAttribute(reinterpret_cast<const void *>(vs_score_kernel<1>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
