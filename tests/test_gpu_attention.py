@@ -113,6 +113,44 @@ def test_bs_ignores_bad_block_ids(B):
     assert_close_rows(o[0], want, "bs bad ids")
 
 
+def token_major(t):
+    """The same values in a [token][head][128] buffer, viewed as [head][token][128]:
+    rows of one head are then n_heads * 256 bytes apart (the kernels' general-stride path)."""
+    return t.transpose(0, 1).contiguous().transpose(0, 1)
+
+
+def test_token_major_layout_bs_vs_dense(B, rng):
+    N, nq, nkv = 1024, 4, 2
+    NB = N // 64
+    q0, k0, v0 = random_qkv(21, nq, nkv, N)
+    q, k, v = token_major(q0), token_major(k0), token_major(v0)
+    assert k.stride(1) == nkv * 128 and q.stride(1) == nq * 128
+    # Block-Sparse
+    heads = [1, 2]
+    idxs = [random_bs_index(rng, NB, 5) for _ in heads]
+    dev = B.bs_index_from_host(np.stack([i for i, _ in idxs]), np.stack([c for _, c in idxs]))
+    o = token_major(torch.full_like(q0, float("nan")))
+    B.minf_bs_attn(q, k, v, o, heads, dev)
+    torch.cuda.synchronize()
+    for r, h in enumerate(heads):
+        want = O.bs_attention(to_f64(q0[h]), to_f64(k0[h // 2]), to_f64(v0[h // 2]), idxs[r][0], idxs[r][1])
+        assert_close_rows(o[h], want, f"token-major bs head {h}")
+    # Vertical-Slash: runs, verticals and a run that ends at the end of the sequence
+    Vl, Sl = list(range(0, N, 37)), [0, 1, 2, 3, 130, 131, 400, 1000]
+    dev = B.vs_index_from_host([Vl, Vl], [Sl, Sl], N)
+    o = token_major(torch.full_like(q0, float("nan")))
+    B.minf_vs_attn(q, k, v, o, [0, 3], dev)
+    torch.cuda.synchronize()
+    for h in (0, 3):
+        want = O.vs_attention(to_f64(q0[h]), to_f64(k0[h // 2]), to_f64(v0[h // 2]), Vl, Sl, Bm=64)
+        assert_close_rows(o[h], want, f"token-major vs head {h}")
+    # dense
+    o = token_major(torch.full_like(q0, float("nan")))
+    B.minf_dense_attn(q, k, v, o, [2])
+    torch.cuda.synchronize()
+    assert_close_rows(o[2], O.dense_attention(to_f64(q0[2]), to_f64(k0[1]), to_f64(v0[1])), "token-major dense")
+
+
 VS_CASES = [
     # (N, verticals, slashes)
     (512, [3, 70, 71, 300, 511], [0, 5, 64, 200, 201, 450]),

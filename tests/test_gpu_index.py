@@ -160,3 +160,18 @@ def test_index_argument_errors(B):
     with pytest.raises(B.MinfError) as e:
         B.minf_build_bs_index(q, k, [0], 4, bidx, ws, block=32)
     assert e.value.status == 5
+
+
+def test_index_builders_token_major_layout(B):
+    """K and Q rows n_heads * 256 bytes apart (the [token][head][128] layout)."""
+    N = 2048
+    q0, k0, v0 = random_qkv(23, 4, 2, N)
+    q = q0.transpose(0, 1).contiguous().transpose(0, 1)
+    k = k0.transpose(0, 1).contiguous().transpose(0, 1)
+    heads = [3, 0]
+    idx = build_vs(B, q, k, heads, 64, 30, 50)
+    for r, h in enumerate(heads):
+        check_vs_index(idx, r, N, to_f64(q0[h]), to_f64(k0[h // 2]), 64, 30, 50)
+    bidx = build_bs(B, q, k, heads, 8)
+    for r, h in enumerate(heads):
+        check_bs_index(bidx, r, to_f64(q0[h]), to_f64(k0[h // 2]), 8)
