@@ -44,7 +44,6 @@
 namespace minf {
 
 constexpr int BS_LIST_CAP = 512;          // block ids staged in LDS per round of the Block-Sparse walk
-constexpr int VS_RUN_CAP = 256;           // slash runs staged in LDS per round of the Vertical-Slash walk
 constexpr int VCAP = 1024;               // compacted vertical columns held in LDS per round
 constexpr float L_LIMIT = 1.2676506e30f;  // 2^100: beyond it the optimistic pass is redone exactly
 
@@ -945,14 +944,17 @@ __global__ __launch_bounds__(256) void ashape_kernel(QKV x, HeadList hl, int n_i
 // One step = 16 global_load_lds instructions (8 K + 8 V); the wave keeps the
 // next step's loads in flight while it computes the current one.
 // ---------------------------------------------------------------------------
-struct StepBuf {
+// K slots first (KD of them: 2, or 3 where the K loads get two iterations to land), then 2 V slots.
+template <int KD>
+struct StepBufT {
   char *lds;
-  __device__ inline char *k(int s) const { return lds + s * 2 * HALF_BYTES; }
-  __device__ inline char *v(int s) const { return lds + s * 2 * HALF_BYTES + HALF_BYTES; }
+  __device__ inline char *k(int s) const { return lds + s * HALF_BYTES; }
+  __device__ inline char *v(int s) const { return lds + (KD + s) * HALF_BYTES; }
 };
+typedef StepBufT<2> StepBuf;
 
-template <bool CONTIG>
-__device__ inline void fetch_step(const StepBuf &sb, int s, const bf16_t *kh, const bf16_t *vh, int64_t k_st,
+template <bool CONTIG, class Buf>
+__device__ inline void fetch_step(const Buf &sb, int s, const bf16_t *kh, const bf16_t *vh, int64_t k_st,
                                   int64_t v_st, int kbase, const int *cols, int N, int lane) {
   DmaLane dk, dv;
   dma_lane_init(dk, k_st, lane);
@@ -1044,14 +1046,14 @@ __device__ inline void dma_pair_gather(const char *head, unsigned rb, const int 
 // generator advances between MFMAs.  When the generator runs dry the loads
 // repeat an earlier step into the free buffer and the MFMAs form logits nobody
 // consumes, so that the body stays one straight path.
-template <class Gen, bool GATHER, bool ROWS256>
+template <class Gen, bool GATHER, bool ROWS256, int KD, int KLAYOUT = KD>
 struct WavePipe {
   Gen &gen;
   WaveState &st;
   const QAcc &qa;
   bool &has_ref;
   const LaneOfs &lo;
-  StepBuf buf;
+  StepBufT<KLAYOUT> buf;
   const char *kh, *vh;       // head bases (bytes)
   unsigned k_rb, v_rb;
   const DmaLane &dk, &dv;
@@ -1059,25 +1061,29 @@ struct WavePipe {
   MaskP mp;
   float c_log2;
   int lane;
-  Step d0, d1, d2;
-  bool h0, h1, h2;
+  Step d0, d1, d2, d3;      // steps t .. t+3 (d3 only with a three-deep K ring)
+  bool h0, h1, h2, h3;
+  int kslot;                // t mod KD
 
   __device__ inline const char *row0(const char *head, unsigned rb, const Step &d) const {
-    // the generators yield steps inside [0, N), the clamp only guards the fetch; step descriptors
-    // come out of LDS lists, i.e. out of vector registers, although they are wave-uniform
-    const int kb = __builtin_amdgcn_readfirstlane(min(max(d.kbase, 0), N - 32));
-    return head + (size_t)kb * rb;
+    // the generators yield steps inside [0, N); step descriptors come out of LDS lists or lanes,
+    // i.e. out of vector registers, although they are wave-uniform
+    const unsigned kb = (unsigned)__builtin_amdgcn_readfirstlane(d.kbase);
+    return head + (uint64_t)kb * rb;
   }
   template <int R>
   __device__ inline void round_dma(const char *kt, const char *vt, const int *kcols, const int *vcols,
                                    unsigned k_dst, unsigned v_dst) const {
-    // K in rounds 0..3, V in rounds 4..7: K is needed at the top of the next iteration, V not
-    // before its round 2
+    // KD == 2: K in rounds 0..3, V in rounds 4..7 (K is needed at the top of the next iteration,
+    // V not before its round 2).  KD == 3: V first, then K, which is not needed before the
+    // iteration after next; the waits count loads in issue order, so what may stay in flight
+    // longest goes out last.
+    constexpr bool k_now = KD == 2 ? R < 4 : R >= 4;
     if (GATHER) {
-      if (R < 4) dma_pair_gather<2 * (R & 3)>(kh, k_rb, kcols, k_dst, lane);
+      if (k_now) dma_pair_gather<2 * (R & 3)>(kh, k_rb, kcols, k_dst, lane);
       else dma_pair_gather<2 * (R & 3)>(vh, v_rb, vcols, v_dst, lane);
     } else {
-      if (R < 4) dma_pair<ROWS256, 2 * (R & 3)>(kt, k_rb, dk.voff, k_dst);
+      if (k_now) dma_pair<ROWS256, 2 * (R & 3)>(kt, k_rb, dk.voff, k_dst);
       else dma_pair<ROWS256, 2 * (R & 3)>(vt, v_rb, dv.voff, v_dst);
     }
   }
@@ -1111,13 +1117,18 @@ struct WavePipe {
   }
 
   __device__ inline void iter(int t, f32x16 (&s_cur)[1][2], f32x16 (&s_nxt)[1][2]) {
-    MINF_WAIT_VMCNT(8);      // K of step t+1 has landed (V of step t, issued after it, may be in flight)
-    const char *tK = buf.k((t + 1) & 1), *tV = buf.v(t & 1);
-    const unsigned k_dst = lds_addr_of(buf.k(t & 1)), v_dst = lds_addr_of(buf.v((t + 1) & 1));
+    // K of step t+1 has landed; still in flight may be, KD == 2: V of step t (issued after it);
+    // KD == 3: V of step t and K of step t+2 (both issued after it)
+    if (KD == 2) MINF_WAIT_VMCNT(8); else MINF_WAIT_VMCNT(16);
+    const int kread = kslot + 1 == KD ? 0 : kslot + 1;              // slot of step t+1; step t+KD goes to kslot
+    const char *tK = buf.k(kread), *tV = buf.v(t & 1);
+    const unsigned k_dst = lds_addr_of(buf.k(kslot)), v_dst = lds_addr_of(buf.v((t + 1) & 1));
+    kslot = kread;
     bf16x8 kf[8], vf[8], p[2][2];
     kf[0] = lds_read_k(tK, lo.k[0]);
-    const char *kt = row0(kh, k_rb, d2), *vt = row0(vh, v_rb, d1);
-    const int *kcols = d2.cols, *vcols = d1.cols;     // the generator advances mid-iteration
+    const Step &dk_src = KD == 2 ? d2 : d3;
+    const char *kt = row0(kh, k_rb, dk_src), *vt = row0(vh, v_rb, d1);
+    const int *kcols = dk_src.cols, *vcols = d1.cols;     // the generator advances mid-iteration
     const float m0 = st.m[0], m1 = st.m[1];
     float lsum0 = 0.f, lsum1 = 0.f;
     auto fetch_v = [&](int i) {            // output update step i = (t, db)
@@ -1125,19 +1136,28 @@ struct WavePipe {
       return lds_read_vt(tV, lo.v[db][0] + base, lo.v[db][1] + base);
     };
     // pair e of the 16 logit pairs per lane, walked [t][nb][r]: P group (nb, t) is
-    // complete after pairs 8t + 4nb .. + 3
-    auto softmax2 = [&](int e) {
-      const int tt = e >> 3, nb = (e >> 2) & 1, r = 8 * tt + 2 * (e & 3);
-      const float m_use = nb == 0 ? m0 : m1;
-      const float e0 = fast_exp2(fmaf(s_cur[0][nb][r], c_log2, -m_use));
-      const float e1 = fast_exp2(fmaf(s_cur[0][nb][r + 1], c_log2, -m_use));
-      if (nb == 0) lsum0 += e0 + e1; else lsum1 += e0 + e1;
-      const f32x2 two = {e0, e1};
+    // complete after pairs 8t + 4nb .. + 3.  The exponentials of pair e are issued
+    // first, the sum and the conversion of pair e - 1 behind them: a transcendental
+    // result is not consumed by the instruction right after it (no wait state).
+    float pe0 = 0.f, pe1 = 0.f;
+    auto finish_pair = [&](int e) {        // pair e's exponentials are in pe0, pe1
+      const int tt = e >> 3, nb = (e >> 2) & 1;
+      if (nb == 0) lsum0 += pe0 + pe1; else lsum1 += pe0 + pe1;
+      const f32x2 two = {pe0, pe1};
       unsigned pk = __builtin_bit_cast(unsigned, __builtin_convertvector(two, bf16x2));
       asm volatile("" : "+v"(pk), "+v"(lsum0), "+v"(lsum1));
       const bf16x2 b2 = __builtin_bit_cast(bf16x2, pk);
       p[nb][tt][2 * (e & 3)] = b2[0];
       p[nb][tt][2 * (e & 3) + 1] = b2[1];
+    };
+    auto softmax2 = [&](int e) {
+      const int tt = e >> 3, nb = (e >> 2) & 1, r = 8 * tt + 2 * (e & 3);
+      const float m_use = nb == 0 ? m0 : m1;
+      float e0 = fast_exp2(fmaf(s_cur[0][nb][r], c_log2, -m_use));
+      float e1 = fast_exp2(fmaf(s_cur[0][nb][r + 1], c_log2, -m_use));
+      asm volatile("" : "+v"(e0), "+v"(e1));
+      if (e > 0) finish_pair(e - 1);
+      pe0 = e0; pe1 = e1;
     };
     auto pv_step = [&](int i) {
       const int tt = i >> 2, db = i & 3;
@@ -1160,7 +1180,9 @@ struct WavePipe {
       constexpr int NEW = (r + 1 < 8 ? 1 : 0) + 2 * NPV_NEXT;      // LDS reads just issued
       __builtin_amdgcn_s_waitcnt(0xC07F | (NEW << 8));
       round_dma<r>(kt, vt, kcols, vcols, k_dst, v_dst);
-      if (r == 1) MINF_WAIT_VMCNT(4);      // V of step t has landed: round 2 starts reading it
+      // V of step t has landed: round 2 starts reading it.  Younger: this iteration's 4 loads so
+      // far and, KD == 3, the 8 K loads that followed V of step t
+      if (r == 1) { if (KD == 2) MINF_WAIT_VMCNT(4); else MINF_WAIT_VMCNT(12); }
       if (r == 0) {
         mfma_qk_first(s_nxt[0][0], kf[0], qa.q[0][0]);
         mfma_qk_first(s_nxt[0][1], kf[0], qa.q[1][0]);
@@ -1171,6 +1193,7 @@ struct WavePipe {
 #pragma unroll
       for (int e = SM0; e < SM1; ++e) {
         softmax2(e);
+        if (e == 15) finish_pair(15);
         if (e + 1 < SM1 || PV0 == PV1) __builtin_amdgcn_sched_barrier(0);
       }
 #pragma unroll
@@ -1182,9 +1205,16 @@ struct WavePipe {
         // advance the generator between MFMAs: the step after d2
         d0 = d1; d1 = d2;
         h0 = h1; h1 = h2;
-        Step dn = d2;
-        h2 = h2 && gen.next(dn);
-        if (h2) d2 = dn;
+        if (KD == 2) {
+          Step dn = d2;
+          h2 = h2 && gen.next(dn);
+          if (h2) d2 = dn;
+        } else {
+          d2 = d3; h2 = h3;
+          Step dn = d3;
+          h3 = h3 && gen.next(dn);
+          if (h3) d3 = dn;
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
     };
@@ -1203,6 +1233,20 @@ struct WavePipe {
     // after the generator advanced in round 3: d0 = the step whose logits are now in s_nxt
     if (h0) fresh(s_nxt, d0);
   }
+  template <bool IS_K>
+  __device__ inline void fetch_whole(const Step &d, unsigned dst) const {
+    const char *head = IS_K ? kh : vh;
+    const unsigned rb = IS_K ? k_rb : v_rb;
+    if (GATHER) {
+      dma_pair_gather<0>(head, rb, d.cols, dst, lane); dma_pair_gather<2>(head, rb, d.cols, dst, lane);
+      dma_pair_gather<4>(head, rb, d.cols, dst, lane); dma_pair_gather<6>(head, rb, d.cols, dst, lane);
+    } else {
+      const char *a = row0(head, rb, d);
+      const unsigned (&vo)[4] = IS_K ? dk.voff : dv.voff;
+      dma_pair<ROWS256, 0>(a, rb, vo, dst); dma_pair<ROWS256, 2>(a, rb, vo, dst);
+      dma_pair<ROWS256, 4>(a, rb, vo, dst); dma_pair<ROWS256, 6>(a, rb, vo, dst);
+    }
+  }
   __device__ inline void run() {
     h0 = gen.next(d0);
     if (!h0) return;
@@ -1210,31 +1254,19 @@ struct WavePipe {
     h1 = gen.next(d1);
     d2 = d1;
     h2 = h1 && gen.next(d2);
-    const unsigned k0 = lds_addr_of(buf.k(0)), k1 = lds_addr_of(buf.k(1)), v0 = lds_addr_of(buf.v(0));
-    {
-      const char *a = row0(kh, k_rb, d0), *b = row0(kh, k_rb, d1), *c = row0(vh, v_rb, d0);
-      // K of steps 0 and 1, V of step 0
-      if (GATHER) {
-        dma_pair_gather<0>(kh, k_rb, d0.cols, k0, lane); dma_pair_gather<2>(kh, k_rb, d0.cols, k0, lane);
-        dma_pair_gather<4>(kh, k_rb, d0.cols, k0, lane); dma_pair_gather<6>(kh, k_rb, d0.cols, k0, lane);
-        dma_pair_gather<0>(kh, k_rb, d1.cols, k1, lane); dma_pair_gather<2>(kh, k_rb, d1.cols, k1, lane);
-        dma_pair_gather<4>(kh, k_rb, d1.cols, k1, lane); dma_pair_gather<6>(kh, k_rb, d1.cols, k1, lane);
-        dma_pair_gather<0>(vh, v_rb, d0.cols, v0, lane); dma_pair_gather<2>(vh, v_rb, d0.cols, v0, lane);
-        dma_pair_gather<4>(vh, v_rb, d0.cols, v0, lane); dma_pair_gather<6>(vh, v_rb, d0.cols, v0, lane);
-      } else {
-        dma_pair<ROWS256, 0>(a, k_rb, dk.voff, k0); dma_pair<ROWS256, 2>(a, k_rb, dk.voff, k0);
-        dma_pair<ROWS256, 4>(a, k_rb, dk.voff, k0); dma_pair<ROWS256, 6>(a, k_rb, dk.voff, k0);
-        dma_pair<ROWS256, 0>(b, k_rb, dk.voff, k1); dma_pair<ROWS256, 2>(b, k_rb, dk.voff, k1);
-        dma_pair<ROWS256, 4>(b, k_rb, dk.voff, k1); dma_pair<ROWS256, 6>(b, k_rb, dk.voff, k1);
-        dma_pair<ROWS256, 0>(c, v_rb, dv.voff, v0); dma_pair<ROWS256, 2>(c, v_rb, dv.voff, v0);
-        dma_pair<ROWS256, 4>(c, v_rb, dv.voff, v0); dma_pair<ROWS256, 6>(c, v_rb, dv.voff, v0);
-      }
-    }
+    d3 = d2;
+    h3 = KD == 3 && h2 && gen.next(d3);
+    // K of steps 0 .. KD-1 into K slots 0 .. KD-1, V of step 0 into V slot 0
+    fetch_whole<true>(d0, lds_addr_of(buf.k(0)));
+    fetch_whole<true>(d1, lds_addr_of(buf.k(1)));
+    if (KD == 3) fetch_whole<true>(d2, lds_addr_of(buf.k(2)));
+    fetch_whole<false>(d0, lds_addr_of(buf.v(0)));
     MINF_WAIT_VMCNT(0);
     f32x16 sa[1][2], sb[1][2];
     qk_first(sa, buf.k(0));
     fresh(sa, d0);
-    // iteration t: d0 = step t (logits in hand), d1 = step t+1 (K landed or landing), d2 = step t+2
+    kslot = 0;
+    // iteration t: d0 = step t (logits in hand), d1 = step t+1 (K landed), d2 = step t+2, d3 = step t+3
     int t = 0;
     while (h0) {
       iter(t, sa, sb);
@@ -1357,7 +1389,7 @@ __global__ __launch_bounds__(64) void bs_kernel(QKV x, HeadList hl, const int32_
     for (int i = lane; i < c.cnt; i += 64) llist[i] = glist[r0 + i];
     __syncthreads();
     BsGen gen{c, mp, 0, 0};
-    WavePipe<BsGen, false, ROWS256> pipe{gen, st, qa, has_ref, lo, c.buf, reinterpret_cast<const char *>(c.kh),
+    WavePipe<BsGen, false, ROWS256, 2> pipe{gen, st, qa, has_ref, lo, c.buf, reinterpret_cast<const char *>(c.kh),
                                          reinterpret_cast<const char *>(c.vh), (unsigned)x.k_st * 2u,
                                          (unsigned)x.v_st * 2u, dk, dv, c.N, mp, c.c_log2, lane};
     pipe.run();
@@ -1390,7 +1422,7 @@ struct VsCtx {
   const int32_t *vlist;
   const int2 *runs;
   const uint32_t *bits;
-  StepBuf buf;
+  StepBufT<3> buf;
   int *cols;
   float c_log2;
 };
@@ -1477,9 +1509,9 @@ __device__ inline void vs_pass(const VsCtx &c, WaveState &st, const LaneOfs &lo,
 }
 
 // Generators of the Vertical-Slash steps for the pipelined pass.
-// Slash runs: a chunk of runs staged in LDS, each walked 32 keys at a time.
+// Slash runs: a chunk of 64 runs held one per lane, each walked 32 keys at a time.
 struct VsRunGen {
-  const int2 *runs;     // LDS
+  int2 mine;            // lane i: run i of the chunk
   int n, q0, N;
   int iv, ks, ke, pos;
   __device__ inline bool next(Step &d) {
@@ -1496,10 +1528,10 @@ struct VsRunGen {
         return true;
       }
       if (iv >= n) return false;
-      const int2 r = runs[iv];
+      const int rx = __builtin_amdgcn_readlane(mine.x, iv), ry = __builtin_amdgcn_readlane(mine.y, iv);
       ++iv;
-      ks = max(q0 - r.y + 1, 0);
-      ke = min(q0 - r.x + 1, N);
+      ks = max(q0 - ry + 1, 0);
+      ke = min(q0 - rx + 1, N);
       pos = ks;
     }
   }
@@ -1522,7 +1554,7 @@ struct VsColGen {
 // Optimistic pass of the Vertical-Slash kernel, software pipelined.
 template <bool ROWS256>
 __device__ inline void vs_pass_pipelined(const VsCtx &c, WaveState &st, const LaneOfs &lo, const MaskP &mp,
-                                         int2 *lruns, int lane) {
+                                         int lane) {
   const int q0 = c.q0;
   bool has_ref = false;
   QAcc qa;
@@ -1532,23 +1564,18 @@ __device__ inline void vs_pass_pipelined(const VsCtx &c, WaveState &st, const La
   dma_lane_init(dv, c.v_st, lane);
   const char *khb = reinterpret_cast<const char *>(c.kh), *vhb = reinterpret_cast<const char *>(c.vh);
   const unsigned k_rb = (unsigned)c.k_st * 2u, v_rb = (unsigned)c.v_st * 2u;
-  // ---- phase A: slash runs, staged VS_RUN_CAP at a time
-  for (int r0 = 0; r0 < c.n_c; r0 += VS_RUN_CAP) {
-    const int n = min(c.n_c - r0, VS_RUN_CAP);
-    if (c.runs[r0].x > q0) break;             // runs ascend: no later run reaches a key >= 0
-    int usable = 0;
-    for (int i = lane; i < n; i += 64) {
-      const int2 r = c.runs[r0 + i];
-      lruns[i] = r;
-      usable += r.x <= q0 ? 1 : 0;
-    }
-    // number of runs of the chunk that reach a key >= 0 (they form a prefix)
-    for (int off = 32; off > 0; off >>= 1) usable += __shfl_xor(usable, off);
-    __syncthreads();
-    VsRunGen gen{lruns, usable, q0, c.N, 0, 0, 0, 0};
-    WavePipe<VsRunGen, false, ROWS256> pipe{gen, st, qa, has_ref, lo, c.buf, khb, vhb, k_rb, v_rb, dk, dv, c.N, mp, c.c_log2, lane};
+  // ---- phase A: slash runs, 64 at a time, one per lane (three-deep K ring: the run list
+  // takes no LDS)
+  for (int r0 = 0; r0 < c.n_c; r0 += 64) {
+    const int n = min(c.n_c - r0, 64);
+    int2 mine = make_int2(KEY_NONE, KEY_NONE);
+    if (lane < n) mine = c.runs[r0 + lane];
+    // runs ascend: those that reach a key >= 0 (t0 <= q0) form a prefix
+    const int usable = __builtin_popcountll(__builtin_amdgcn_ballot_w64(lane < n && mine.x <= q0));
+    if (usable == 0) break;
+    VsRunGen gen{mine, usable, q0, c.N, 0, 0, 0, 0};
+    WavePipe<VsRunGen, false, ROWS256, 3> pipe{gen, st, qa, has_ref, lo, c.buf, khb, vhb, k_rb, v_rb, dk, dv, c.N, mp, c.c_log2, lane};
     pipe.run();
-    __syncthreads();
     if (usable < n) break;
   }
   // ---- phase B: verticals
@@ -1577,7 +1604,7 @@ __device__ inline void vs_pass_pipelined(const VsCtx &c, WaveState &st, const La
     if (lane + ncol < nstep * 32) cols[ncol + lane] = KEY_NONE;   // pad the last step
     __syncthreads();
     VsColGen gen{cols, nstep, q0, 0};
-    WavePipe<VsColGen, true, ROWS256> pipe{gen, st, qa, has_ref, lo, c.buf, khb, vhb, k_rb, v_rb, dk, dv, c.N, mp, c.c_log2, lane};
+    WavePipe<VsColGen, true, ROWS256, 2, 3> pipe{gen, st, qa, has_ref, lo, c.buf, khb, vhb, k_rb, v_rb, dk, dv, c.N, mp, c.c_log2, lane};
     pipe.run();
     __syncthreads();
   }
@@ -1601,8 +1628,10 @@ __global__ __launch_bounds__(64) void vs_kernel(QKV x, HeadList hl, const int32_
 
   VsCtx c;
   c.kh = x.k + kvh * x.k_sh; c.vh = x.v + kvh * x.v_sh; c.k_st = x.k_st; c.v_st = x.v_st;
-  c.N = x.N; c.q0 = q0; c.buf = StepBuf{lds}; c.c_log2 = x.c_log2;
-  c.cols = reinterpret_cast<int *>(lds + 4 * HALF_BYTES);   // [VCAP + 64]
+  // LDS: K slots 0..2, V slots 0..1 (40 KiB, four workgroups fill a CU's 160 KiB).  The column
+  // list of the vertical phase, which runs on K slots 0 and 1 only, lives in K slot 2.
+  c.N = x.N; c.q0 = q0; c.buf = StepBufT<3>{lds}; c.c_log2 = x.c_log2;
+  c.cols = reinterpret_cast<int *>(lds + 2 * HALF_BYTES);   // [VCAP + 64]
   c.n_v = min(max(counts[slot * 4 + 0], 0), nv);
   c.n_c = min(max(counts[slot * 4 + 2], 0), ns);
   c.vlist = v_idx + (int64_t)slot * nv;
@@ -1616,7 +1645,7 @@ __global__ __launch_bounds__(64) void vs_kernel(QKV x, HeadList hl, const int32_
   MaskP mp;
   mp.q0 = q0; mp.n_init = KEY_NONE; mp.n_local = 1; mp.lo = 0; mp.hi = 0;
 
-  vs_pass_pipelined<ROWS256>(c, st, lo, mp, reinterpret_cast<int2 *>(c.cols + VCAP + 64), lane);
+  vs_pass_pipelined<ROWS256>(c, st, lo, mp, lane);
   if (needs_exact(st)) {
     load_q(st, qh, x.q_st, q0, lane);   // the pipelined pass kept Q in accumulator registers only
     reset_for_max_pass(st);
@@ -1673,7 +1702,7 @@ hipError_t launch_vs(const QKV &x, const HeadList &hl, const int32_t *v_idx, con
                      int cover_words, hipStream_t st) {
   const int NB = x.N / BQ;
   const Sched s = make_sched(hl.n, NB);
-  const size_t lds = 4 * HALF_BYTES + (VCAP + 64) * sizeof(int) + VS_RUN_CAP * sizeof(int2);
+  const size_t lds = 5 * HALF_BYTES;
   // gathered rows are addressed with 32-bit byte offsets from the head base
   if ((uint64_t)x.N * (uint64_t)x.k_st * 2u >= (1ull << 32) || (uint64_t)x.N * (uint64_t)x.v_st * 2u >= (1ull << 32))
     return hipErrorInvalidValue;
