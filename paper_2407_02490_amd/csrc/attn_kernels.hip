@@ -43,7 +43,6 @@
 
 namespace minf {
 
-constexpr int BS_LIST_CAP = 512;          // block ids staged in LDS per round of the Block-Sparse walk
 constexpr int VCAP = 1024;               // compacted vertical columns held in LDS per round
 constexpr float L_LIMIT = 1.2676506e30f;  // 2^100: beyond it the optimistic pass is redone exactly
 
@@ -944,14 +943,13 @@ __global__ __launch_bounds__(256) void ashape_kernel(QKV x, HeadList hl, int n_i
 // One step = 16 global_load_lds instructions (8 K + 8 V); the wave keeps the
 // next step's loads in flight while it computes the current one.
 // ---------------------------------------------------------------------------
-// K slots first (KD of them: 2, or 3 where the K loads get two iterations to land), then 2 V slots.
-template <int KD>
-struct StepBufT {
+// Per-wave LDS ring of the single-wave kernels: K slots 0, 1, then V slots 0, 1, 2 (8 KiB each,
+// 40 KiB: four workgroups fill a CU's 160 KiB).  The two-deep pipelines use V slots 0 and 1.
+struct StepBuf {
   char *lds;
   __device__ inline char *k(int s) const { return lds + s * HALF_BYTES; }
-  __device__ inline char *v(int s) const { return lds + (KD + s) * HALF_BYTES; }
+  __device__ inline char *v(int s) const { return lds + (2 + s) * HALF_BYTES; }
 };
-typedef StepBufT<2> StepBuf;
 
 template <bool CONTIG, class Buf>
 __device__ inline void fetch_step(const Buf &sb, int s, const bf16_t *kh, const bf16_t *vh, int64_t k_st,
@@ -1046,14 +1044,14 @@ __device__ inline void dma_pair_gather(const char *head, unsigned rb, const int 
 // generator advances between MFMAs.  When the generator runs dry the loads
 // repeat an earlier step into the free buffer and the MFMAs form logits nobody
 // consumes, so that the body stays one straight path.
-template <class Gen, bool GATHER, bool ROWS256, int KD, int KLAYOUT = KD>
+template <class Gen, bool GATHER, bool ROWS256>
 struct WavePipe {
   Gen &gen;
   WaveState &st;
   const QAcc &qa;
   bool &has_ref;
   const LaneOfs &lo;
-  StepBufT<KLAYOUT> buf;
+  StepBuf buf;
   const char *kh, *vh;       // head bases (bytes)
   unsigned k_rb, v_rb;
   const DmaLane &dk, &dv;
@@ -1061,9 +1059,8 @@ struct WavePipe {
   MaskP mp;
   float c_log2;
   int lane;
-  Step d0, d1, d2, d3;      // steps t .. t+3 (d3 only with a three-deep K ring)
-  bool h0, h1, h2, h3;
-  int kslot;                // t mod KD
+  Step d0, d1, d2;          // steps t, t+1, t+2
+  bool h0, h1, h2;
 
   __device__ inline const char *row0(const char *head, unsigned rb, const Step &d) const {
     // the generators yield steps inside [0, N); step descriptors come out of LDS lists or lanes,
@@ -1074,11 +1071,9 @@ struct WavePipe {
   template <int R>
   __device__ inline void round_dma(const char *kt, const char *vt, const int *kcols, const int *vcols,
                                    unsigned k_dst, unsigned v_dst) const {
-    // KD == 2: K in rounds 0..3, V in rounds 4..7 (K is needed at the top of the next iteration,
-    // V not before its round 2).  KD == 3: V first, then K, which is not needed before the
-    // iteration after next; the waits count loads in issue order, so what may stay in flight
-    // longest goes out last.
-    constexpr bool k_now = KD == 2 ? R < 4 : R >= 4;
+    // K in rounds 0..3, V in rounds 4..7: K is needed at the top of the next iteration, V not
+    // before its round 2
+    constexpr bool k_now = R < 4;
     if (GATHER) {
       if (k_now) dma_pair_gather<2 * (R & 3)>(kh, k_rb, kcols, k_dst, lane);
       else dma_pair_gather<2 * (R & 3)>(vh, v_rb, vcols, v_dst, lane);
@@ -1117,18 +1112,13 @@ struct WavePipe {
   }
 
   __device__ inline void iter(int t, f32x16 (&s_cur)[1][2], f32x16 (&s_nxt)[1][2]) {
-    // K of step t+1 has landed; still in flight may be, KD == 2: V of step t (issued after it);
-    // KD == 3: V of step t and K of step t+2 (both issued after it)
-    if (KD == 2) MINF_WAIT_VMCNT(8); else MINF_WAIT_VMCNT(16);
-    const int kread = kslot + 1 == KD ? 0 : kslot + 1;              // slot of step t+1; step t+KD goes to kslot
-    const char *tK = buf.k(kread), *tV = buf.v(t & 1);
-    const unsigned k_dst = lds_addr_of(buf.k(kslot)), v_dst = lds_addr_of(buf.v((t + 1) & 1));
-    kslot = kread;
+    MINF_WAIT_VMCNT(8);      // K of step t+1 has landed (V of step t, issued after it, may be in flight)
+    const char *tK = buf.k((t + 1) & 1), *tV = buf.v(t & 1);
+    const unsigned k_dst = lds_addr_of(buf.k(t & 1)), v_dst = lds_addr_of(buf.v((t + 1) & 1));
     bf16x8 kf[8], vf[8], p[2][2];
     kf[0] = lds_read_k(tK, lo.k[0]);
-    const Step &dk_src = KD == 2 ? d2 : d3;
-    const char *kt = row0(kh, k_rb, dk_src), *vt = row0(vh, v_rb, d1);
-    const int *kcols = dk_src.cols, *vcols = d1.cols;     // the generator advances mid-iteration
+    const char *kt = row0(kh, k_rb, d2), *vt = row0(vh, v_rb, d1);
+    const int *kcols = d2.cols, *vcols = d1.cols;     // the generator advances mid-iteration
     const float m0 = st.m[0], m1 = st.m[1];
     float lsum0 = 0.f, lsum1 = 0.f;
     auto fetch_v = [&](int i) {            // output update step i = (t, db)
@@ -1180,9 +1170,7 @@ struct WavePipe {
       constexpr int NEW = (r + 1 < 8 ? 1 : 0) + 2 * NPV_NEXT;      // LDS reads just issued
       __builtin_amdgcn_s_waitcnt(0xC07F | (NEW << 8));
       round_dma<r>(kt, vt, kcols, vcols, k_dst, v_dst);
-      // V of step t has landed: round 2 starts reading it.  Younger: this iteration's 4 loads so
-      // far and, KD == 3, the 8 K loads that followed V of step t
-      if (r == 1) { if (KD == 2) MINF_WAIT_VMCNT(4); else MINF_WAIT_VMCNT(12); }
+      if (r == 1) MINF_WAIT_VMCNT(4);      // V of step t has landed: round 2 starts reading it
       if (r == 0) {
         mfma_qk_first(s_nxt[0][0], kf[0], qa.q[0][0]);
         mfma_qk_first(s_nxt[0][1], kf[0], qa.q[1][0]);
@@ -1205,16 +1193,9 @@ struct WavePipe {
         // advance the generator between MFMAs: the step after d2
         d0 = d1; d1 = d2;
         h0 = h1; h1 = h2;
-        if (KD == 2) {
-          Step dn = d2;
-          h2 = h2 && gen.next(dn);
-          if (h2) d2 = dn;
-        } else {
-          d2 = d3; h2 = h3;
-          Step dn = d3;
-          h3 = h3 && gen.next(dn);
-          if (h3) d3 = dn;
-        }
+        Step dn = d2;
+        h2 = h2 && gen.next(dn);
+        if (h2) d2 = dn;
       }
       __builtin_amdgcn_sched_barrier(0);
     };
@@ -1254,24 +1235,230 @@ struct WavePipe {
     h1 = gen.next(d1);
     d2 = d1;
     h2 = h1 && gen.next(d2);
-    d3 = d2;
-    h3 = KD == 3 && h2 && gen.next(d3);
-    // K of steps 0 .. KD-1 into K slots 0 .. KD-1, V of step 0 into V slot 0
+    // K of steps 0, 1 into K slots 0, 1, V of step 0 into V slot 0
     fetch_whole<true>(d0, lds_addr_of(buf.k(0)));
     fetch_whole<true>(d1, lds_addr_of(buf.k(1)));
-    if (KD == 3) fetch_whole<true>(d2, lds_addr_of(buf.k(2)));
     fetch_whole<false>(d0, lds_addr_of(buf.v(0)));
     MINF_WAIT_VMCNT(0);
     f32x16 sa[1][2], sb[1][2];
     qk_first(sa, buf.k(0));
     fresh(sa, d0);
-    kslot = 0;
-    // iteration t: d0 = step t (logits in hand), d1 = step t+1 (K landed), d2 = step t+2, d3 = step t+3
+    // iteration t: d0 = step t (logits in hand), d1 = step t+1 (K landed), d2 = step t+2
     int t = 0;
     while (h0) {
       iter(t, sa, sb);
       if (!h0) break;
       iter(t + 1, sb, sa);
+      t += 2;
+    }
+    MINF_WAIT_VMCNT(0);      // the repeated loads of the last iterations
+  }
+};
+
+// Three steps in flight per iteration, for contiguous steps: the matrix cores
+// alternate between the logits of step t+1 (K Q^T) and the output update of
+// step t-1 (V^T P^T) while the vector ALU turns the logits of step t into P(t).
+// Every round then has the same mix -- 2 + 2 MFMAs, 2 logit pairs, 3 LDS reads,
+// 2 tile loads -- which the two-deep scheme above cannot offer (its first rounds
+// are all softmax, its last all MFMA, and one wave per SIMD issues in order).
+// Price: V of step t-1 is read while V of step t waits and V of step t+1 lands:
+// three V slots.  Iteration t issues K of step t+2 (rounds 0..3, needed at the
+// top of iteration t+1) and then V of step t+1 (rounds 4..7, needed in
+// iteration t+2); the single wait at the top leaves the 8 V loads in flight.
+// The body is one straight path: without a current step P = 0 (infinite
+// reference), without a next step the MFMAs form logits nobody consumes and
+// the loads repeat an earlier step into the free slots; the first iteration
+// multiplies a zero P(-1) with V(0).
+template <class Gen, bool ROWS256>
+struct WavePipe3 {
+  Gen &gen;
+  WaveState &st;
+  const QAcc &qa;
+  bool &has_ref;
+  const LaneOfs &lo;
+  StepBuf buf;
+  const char *kh, *vh;       // head bases (bytes)
+  unsigned k_rb, v_rb;
+  const DmaLane &dk, &dv;
+  MaskP mp;
+  float c_log2;
+  int lane;
+  Step d0, d1, d2;          // steps t (softmax), t+1 (logits), t+2 (K fetch)
+  bool h0, h1, h2, hp;      // ... exist; hp: step t-1 exists (its P awaits the output update)
+  unsigned v0, v1, v2;      // LDS byte offsets of the V slots of steps t-1, t, t+1
+
+  __device__ inline const char *row0(const char *head, unsigned rb, const Step &d) const {
+    const unsigned kb = (unsigned)__builtin_amdgcn_readfirstlane(d.kbase);
+    return head + (uint64_t)kb * rb;
+  }
+  __device__ inline void fresh(f32x16 (&s)[1][2], const Step &d) {
+    if (d.cls == 2 || !has_ref) {
+      MaskP m = mp;
+      m.lo = d.lo; m.hi = d.hi;
+      if (d.cls == 2) window_mask<1>(s, d.kbase, m, lane);
+      if (!has_ref) special_tile<1>(s, st, d.kbase, m, false, true, c_log2, lane);
+    }
+    has_ref = true;
+  }
+  __device__ inline void qk_first(f32x16 (&s)[1][2], const char *tK) const {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const bf16x8 a = lds_read_k(tK, lo.k[ks]);
+      if (ks == 0) {
+        mfma_qk_first(s[0][0], a, qa.q[0][0]);
+        mfma_qk_first(s[0][1], a, qa.q[1][0]);
+      } else {
+        mfma_qk_acc(s[0][0], a, qa.q[0][ks]);
+        mfma_qk_acc(s[0][1], a, qa.q[1][ks]);
+      }
+    }
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");   // results readable by the vector ALU
+  }
+  template <bool IS_K>
+  __device__ inline void fetch_whole(const Step &d, unsigned dst) const {
+    const char *a = row0(IS_K ? kh : vh, IS_K ? k_rb : v_rb, d);
+    const unsigned rb = IS_K ? k_rb : v_rb;
+    const unsigned (&vo)[4] = IS_K ? dk.voff : dv.voff;
+    dma_pair<ROWS256, 0>(a, rb, vo, dst); dma_pair<ROWS256, 2>(a, rb, vo, dst);
+    dma_pair<ROWS256, 4>(a, rb, vo, dst); dma_pair<ROWS256, 6>(a, rb, vo, dst);
+  }
+
+  __device__ inline void iter(int t, f32x16 (&s_cur)[1][2], f32x16 (&s_nxt)[1][2], bf16x8 (&p_prev)[2][2],
+                              bf16x8 (&p_cur)[2][2]) {
+    MINF_WAIT_VMCNT(8);      // K of step t+1 (and everything older) has landed; V of step t may be in flight
+    const char *tK = buf.k((t + 1) & 1);
+    const char *tV = buf.lds + (t == 0 ? v1 : v0);        // no step -1: zero P times the rows of V(0)
+    const unsigned k_dst = lds_addr_of(buf.k(t & 1)), v_dst = lds_addr_of(buf.lds) + v2;
+    const char *kt = row0(kh, k_rb, d2), *vt = row0(vh, v_rb, d1);
+    bf16x8 kf[8], vf[8];
+    kf[0] = lds_read_k(tK, lo.k[0]);
+    auto fetch_v = [&](int i) {            // output update step i = (t, db)
+      const int base = 16 * (i >> 2) * ROW_BYTES, db = i & 3;
+      return lds_read_vt(tV, lo.v[db][0] + base, lo.v[db][1] + base);
+    };
+    vf[0] = fetch_v(0);
+    const bool attend = h0;
+    // no current step: infinite reference, P = exp2(-inf) = 0
+    const float m0 = attend ? st.m[0] : INFINITY, m1 = attend ? st.m[1] : INFINITY;
+    float lsum0 = 0.f, lsum1 = 0.f;
+    // Pair e of the 16 logit pairs per lane, walked [t][nb][r]: round r handles pairs 2r, 2r + 1,
+    // so that P(t) group (nb, tt) is born in the rounds in which P(t-1) group (., tt) is last used
+    // and the two generations of P share registers.  The exponentials of pair e are issued first,
+    // the sum and the conversion of pair e - 1 behind them (no wait state after a transcendental).
+    float pe0 = 0.f, pe1 = 0.f;
+    auto finish_pair = [&](int e) {        // pair e's exponentials are in pe0, pe1
+      const int tt = e >> 3, nb = (e >> 2) & 1;
+      if (nb == 0) lsum0 += pe0 + pe1; else lsum1 += pe0 + pe1;
+      const f32x2 two = {pe0, pe1};
+      unsigned pk = __builtin_bit_cast(unsigned, __builtin_convertvector(two, bf16x2));
+      asm volatile("" : "+v"(pk), "+v"(lsum0), "+v"(lsum1));
+      const bf16x2 b2 = __builtin_bit_cast(bf16x2, pk);
+      p_cur[nb][tt][2 * (e & 3)] = b2[0];
+      p_cur[nb][tt][2 * (e & 3) + 1] = b2[1];
+    };
+    // the two halves of a pair's work: exponentials of pair e; sum and conversion of the pair before
+    float ne0 = 0.f, ne1 = 0.f;
+    auto exp_pair = [&](int e) {
+      const int tt = e >> 3, nb = (e >> 2) & 1, r = 8 * tt + 2 * (e & 3);
+      const float m_use = nb == 0 ? m0 : m1;
+      ne0 = fast_exp2(fmaf(s_cur[0][nb][r], c_log2, -m_use));
+      ne1 = fast_exp2(fmaf(s_cur[0][nb][r + 1], c_log2, -m_use));
+      asm volatile("" : "+v"(ne0), "+v"(ne1));
+    };
+    auto sum_pair = [&](int e) {           // finishes pair e - 1, then pair e's exponentials take its place
+      if (e > 0) finish_pair(e - 1);
+      pe0 = ne0; pe1 = ne1;
+    };
+    // One round = 4 groups, each opened by ONE MFMA and filled with about a quarter of the round's
+    // other instructions: the wave issues in order, and a second MFMA right behind the first would
+    // stall the issue for the 32 cycles the first occupies the pipeline -- time that is lost when
+    // the round is bound by instruction issue, as it is here.
+    auto round = [&](auto rc_) {
+      constexpr int r = decltype(rc_)::value;
+      // group 0: logits, query block 0; exponentials of pair 2r
+      if (r == 0) mfma_qk_first(s_nxt[0][0], kf[0], qa.q[0][0]);
+      else mfma_qk_acc(s_nxt[0][0], kf[r], qa.q[0][r]);
+      exp_pair(2 * r);
+      if (r + 1 < 8) kf[(r + 1) & 7] = lds_read_k(tK, lo.k[(r + 1) & 7]);
+      __builtin_amdgcn_sched_barrier(0);
+      // group 1: logits, query block 1; sum / conversion of pair 2r - 1; the round's two tile loads
+      if (r == 0) mfma_qk_first(s_nxt[0][1], kf[0], qa.q[1][0]);
+      else mfma_qk_acc(s_nxt[0][1], kf[r], qa.q[1][r]);
+      sum_pair(2 * r);
+      if (r < 4) dma_pair<ROWS256, 2 * (r & 3)>(kt, k_rb, dk.voff, k_dst);
+      else dma_pair<ROWS256, 2 * (r & 3)>(vt, v_rb, dv.voff, v_dst);
+      __builtin_amdgcn_sched_barrier(0);
+      // group 2: output update step r, query block 0; exponentials of pair 2r + 1
+      {
+        const int tt = r >> 2, db = r & 3;
+        st.o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[r], p_prev[0][tt], st.o[db][0], 0, 0, 0);
+      }
+      exp_pair(2 * r + 1);
+      if (r + 1 < 8) vf[(r + 1) & 7] = fetch_v((r + 1) & 7);
+      __builtin_amdgcn_sched_barrier(0);
+      // group 3: output update step r, query block 1; sum / conversion of pair 2r; bookkeeping
+      {
+        const int tt = r >> 2, db = r & 3;
+        st.o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[r], p_prev[1][tt], st.o[db][1], 0, 0, 0);
+      }
+      sum_pair(2 * r + 1);
+      if (r == 7) finish_pair(15);
+      if (r == 3) {
+        // advance the generator between MFMAs
+        hp = h0;
+        d0 = d1; d1 = d2;
+        h0 = h1; h1 = h2;
+        Step dn = d2;
+        h2 = h2 && gen.next(dn);
+        if (h2) d2 = dn;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    round(std::integral_constant<int, 0>{});
+    round(std::integral_constant<int, 1>{});
+    round(std::integral_constant<int, 2>{});
+    round(std::integral_constant<int, 3>{});
+    round(std::integral_constant<int, 4>{});
+    round(std::integral_constant<int, 5>{});
+    round(std::integral_constant<int, 6>{});
+    round(std::integral_constant<int, 7>{});
+    if (attend) {
+      st.l[0] += lsum0;
+      st.l[1] += lsum1;
+    }
+    // after the generator advanced in round 3: d0 = the step whose logits are now in s_nxt
+    if (h0) fresh(s_nxt, d0);
+    const unsigned vr = v0; v0 = v1; v1 = v2; v2 = vr;
+  }
+  __device__ inline void run() {
+    h0 = gen.next(d0);
+    if (!h0) return;
+    d1 = d0;
+    h1 = gen.next(d1);
+    d2 = d1;
+    h2 = h1 && gen.next(d2);
+    hp = false;
+    v0 = 2 * HALF_BYTES; v1 = 3 * HALF_BYTES; v2 = 4 * HALF_BYTES;
+    // K of steps 0, 1 into K slots 0, 1; V of step 0 into the slot of "step t" of iteration 0
+    fetch_whole<true>(d0, lds_addr_of(buf.k(0)));
+    fetch_whole<true>(d1, lds_addr_of(buf.k(1)));
+    fetch_whole<false>(d0, lds_addr_of(buf.lds) + v1);
+    MINF_WAIT_VMCNT(0);
+    f32x16 sa[1][2], sb[1][2];
+    bf16x8 pa[2][2], pb[2][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) (&pa[0][0])[i][j] = (__bf16)0.f;
+    qk_first(sa, buf.k(0));
+    fresh(sa, d0);
+    // iteration t: d0 = step t (logits in hand), d1 = step t+1 (K landed), d2 = step t+2;
+    // one iteration past the last step finishes its output update
+    int t = 0;
+    while (h0 || hp) {
+      iter(t, sa, sb, pa, pb);
+      if (!(h0 || hp)) break;
+      iter(t + 1, sb, sa, pb, pa);
       t += 2;
     }
     MINF_WAIT_VMCNT(0);      // the repeated loads of the last iterations
@@ -1325,13 +1512,14 @@ __device__ inline void bs_pass(const BsCtx &c, WaveState &st, const LaneOfs &lo,
 // holds a key some row may attend (ids outside [0, NB) and blocks past the
 // diagonal are dropped).
 struct BsGen {
-  const BsCtx &c;
+  int mine;             // lane i: entry i of the current chunk of the block list
+  int n, NB;
   const MaskP &mp;
   int i, half;
   __device__ inline bool next(Step &d) {
-    while (i < c.cnt) {
-      const int b = c.list[i];
-      if (b >= 0 && b < c.NB) {
+    while (i < n) {
+      const int b = __builtin_amdgcn_readlane(mine, i);
+      if (b >= 0 && b < NB) {
         const int kbase = b * BK + 32 * half;
         const int cls = classify_step<32>(kbase, mp);
         if (half == 1) { ++i; half = 0; } else half = 1;
@@ -1370,12 +1558,10 @@ __global__ __launch_bounds__(64) void bs_kernel(QKV x, HeadList hl, const int32_
   BsCtx c;
   c.kh = x.k + kvh * x.k_sh; c.vh = x.v + kvh * x.v_sh; c.k_st = x.k_st; c.v_st = x.v_st;
   c.N = x.N; c.NB = NB; c.buf = StepBuf{lds}; c.c_log2 = x.c_log2;
-  // the block list of this query block is staged in LDS (at most BS_LIST_CAP ids per
-  // round of the walk) so that the step generator never waits on global memory
+  // the block list of this query block is walked 64 ids at a time, one per lane
   const int32_t *glist = blk_idx + ((int64_t)slot * NB + b) * topk;
   c.cnt = min(max(blk_cnt[(int64_t)slot * NB + b], 0), topk);
-  int *llist = reinterpret_cast<int *>(lds + 4 * HALF_BYTES);
-  c.list = llist;
+  c.list = glist;
 
   QAcc qa;
   pin_q(qa, st);
@@ -1384,20 +1570,16 @@ __global__ __launch_bounds__(64) void bs_kernel(QKV x, HeadList hl, const int32_
   dma_lane_init(dv, x.v_st, lane);
   const int total = c.cnt;
   bool has_ref = false;
-  for (int r0 = 0; r0 < total; r0 += BS_LIST_CAP) {
-    c.cnt = min(total - r0, BS_LIST_CAP);
-    for (int i = lane; i < c.cnt; i += 64) llist[i] = glist[r0 + i];
-    __syncthreads();
-    BsGen gen{c, mp, 0, 0};
-    WavePipe<BsGen, false, ROWS256, 2> pipe{gen, st, qa, has_ref, lo, c.buf, reinterpret_cast<const char *>(c.kh),
-                                         reinterpret_cast<const char *>(c.vh), (unsigned)x.k_st * 2u,
-                                         (unsigned)x.v_st * 2u, dk, dv, c.N, mp, c.c_log2, lane};
+  for (int r0 = 0; r0 < total; r0 += 64) {
+    const int n = min(total - r0, 64);
+    const int mine = lane < n ? glist[r0 + lane] : -1;
+    BsGen gen{mine, n, NB, mp, 0, 0};
+    WavePipe3<BsGen, ROWS256> pipe{gen, st, qa, has_ref, lo, c.buf, reinterpret_cast<const char *>(c.kh),
+                                   reinterpret_cast<const char *>(c.vh), (unsigned)x.k_st * 2u,
+                                   (unsigned)x.v_st * 2u, dk, dv, mp, c.c_log2, lane};
     pipe.run();
-    __syncthreads();
   }
   if (needs_exact(st)) {
-    c.list = glist;
-    c.cnt = total;
     load_q(st, qh, x.q_st, q0, lane);   // the pipelined pass kept Q in accumulator registers only
     reset_for_max_pass(st);
     bs_pass<PASS_MAX>(c, st, lo, mp, lane);
@@ -1422,7 +1604,7 @@ struct VsCtx {
   const int32_t *vlist;
   const int2 *runs;
   const uint32_t *bits;
-  StepBufT<3> buf;
+  StepBuf buf;
   int *cols;
   float c_log2;
 };
@@ -1564,8 +1746,7 @@ __device__ inline void vs_pass_pipelined(const VsCtx &c, WaveState &st, const La
   dma_lane_init(dv, c.v_st, lane);
   const char *khb = reinterpret_cast<const char *>(c.kh), *vhb = reinterpret_cast<const char *>(c.vh);
   const unsigned k_rb = (unsigned)c.k_st * 2u, v_rb = (unsigned)c.v_st * 2u;
-  // ---- phase A: slash runs, 64 at a time, one per lane (three-deep K ring: the run list
-  // takes no LDS)
+  // ---- phase A: slash runs, 64 at a time, one per lane (the run list takes no LDS)
   for (int r0 = 0; r0 < c.n_c; r0 += 64) {
     const int n = min(c.n_c - r0, 64);
     int2 mine = make_int2(KEY_NONE, KEY_NONE);
@@ -1574,7 +1755,7 @@ __device__ inline void vs_pass_pipelined(const VsCtx &c, WaveState &st, const La
     const int usable = __builtin_popcountll(__builtin_amdgcn_ballot_w64(lane < n && mine.x <= q0));
     if (usable == 0) break;
     VsRunGen gen{mine, usable, q0, c.N, 0, 0, 0, 0};
-    WavePipe<VsRunGen, false, ROWS256, 3> pipe{gen, st, qa, has_ref, lo, c.buf, khb, vhb, k_rb, v_rb, dk, dv, c.N, mp, c.c_log2, lane};
+    WavePipe3<VsRunGen, ROWS256> pipe{gen, st, qa, has_ref, lo, c.buf, khb, vhb, k_rb, v_rb, dk, dv, mp, c.c_log2, lane};
     pipe.run();
     if (usable < n) break;
   }
@@ -1604,7 +1785,7 @@ __device__ inline void vs_pass_pipelined(const VsCtx &c, WaveState &st, const La
     if (lane + ncol < nstep * 32) cols[ncol + lane] = KEY_NONE;   // pad the last step
     __syncthreads();
     VsColGen gen{cols, nstep, q0, 0};
-    WavePipe<VsColGen, true, ROWS256, 2, 3> pipe{gen, st, qa, has_ref, lo, c.buf, khb, vhb, k_rb, v_rb, dk, dv, c.N, mp, c.c_log2, lane};
+    WavePipe<VsColGen, true, ROWS256> pipe{gen, st, qa, has_ref, lo, c.buf, khb, vhb, k_rb, v_rb, dk, dv, c.N, mp, c.c_log2, lane};
     pipe.run();
     __syncthreads();
   }
@@ -1628,10 +1809,9 @@ __global__ __launch_bounds__(64) void vs_kernel(QKV x, HeadList hl, const int32_
 
   VsCtx c;
   c.kh = x.k + kvh * x.k_sh; c.vh = x.v + kvh * x.v_sh; c.k_st = x.k_st; c.v_st = x.v_st;
-  // LDS: K slots 0..2, V slots 0..1 (40 KiB, four workgroups fill a CU's 160 KiB).  The column
-  // list of the vertical phase, which runs on K slots 0 and 1 only, lives in K slot 2.
-  c.N = x.N; c.q0 = q0; c.buf = StepBufT<3>{lds}; c.c_log2 = x.c_log2;
-  c.cols = reinterpret_cast<int *>(lds + 2 * HALF_BYTES);   // [VCAP + 64]
+  // The column list of the vertical phase, which runs two deep on V slots 0 and 1, lives in V slot 2.
+  c.N = x.N; c.q0 = q0; c.buf = StepBuf{lds}; c.c_log2 = x.c_log2;
+  c.cols = reinterpret_cast<int *>(lds + 4 * HALF_BYTES);   // [VCAP + 64]
   c.n_v = min(max(counts[slot * 4 + 0], 0), nv);
   c.n_c = min(max(counts[slot * 4 + 2], 0), ns);
   c.vlist = v_idx + (int64_t)slot * nv;
@@ -1684,7 +1864,7 @@ hipError_t launch_bs(const QKV &x, const HeadList &hl, const int32_t *blk_idx, c
                      int topk, hipStream_t st) {
   const int NB = x.N / BQ;
   const Sched s = make_sched(hl.n, NB);
-  const size_t lds = 4 * HALF_BYTES + BS_LIST_CAP * sizeof(int);
+  const size_t lds = 5 * HALF_BYTES;
   const bool rows256 = x.k_st == D && x.v_st == D;
   const void *fn = rows256 ? reinterpret_cast<const void *>(bs_kernel<true>)
                            : reinterpret_cast<const void *>(bs_kernel<false>);
