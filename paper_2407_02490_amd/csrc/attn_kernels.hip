@@ -758,57 +758,74 @@ struct AshapeLoop {
     // group j = (mb, t) and query block nb into one B operand of the output
     // update: P(t) group j is born in the rounds in which P(t-1) group j is last
     // used, so the two generations of P share registers (about 40 instead of 64).
-    auto softmax2 = [&](int e) {           // e = 8 * round + 2 * group
+    // Pair e (even) of the 64 logits per lane: exponentials first; sum and conversion follow one
+    // pair later, so that no instruction consumes a transcendental result right behind it.
+    float pe0 = 0.f, pe1 = 0.f, ne0 = 0.f, ne1 = 0.f;
+    auto exp_pair = [&](int e) {
       const int j = e / 16, nb = (e / 8) & 1, mb = j / 2, r = 8 * (j & 1) + (e & 7);
       const float m_use = nb == 0 ? m0 : m1;
-      const float e0 = fast_exp2(fmaf(s_cur[mb][nb][r], c_log2, -m_use));
-      const float e1 = fast_exp2(fmaf(s_cur[mb][nb][r + 1], c_log2, -m_use));
-      if (nb == 0) lsum0 += e0 + e1; else lsum1 += e0 + e1;
-      const f32x2 two = {e0, e1};
+      ne0 = fast_exp2(fmaf(s_cur[mb][nb][r], c_log2, -m_use));
+      ne1 = fast_exp2(fmaf(s_cur[mb][nb][r + 1], c_log2, -m_use));
+      asm volatile("" : "+v"(ne0), "+v"(ne1));
+    };
+    auto finish_pair = [&](int e) {        // pair e's exponentials are in pe0, pe1
+      const int j = e / 16, nb = (e / 8) & 1, mb = j / 2, r = 8 * (j & 1) + (e & 7);
+      if (nb == 0) lsum0 += pe0 + pe1; else lsum1 += pe0 + pe1;
+      const f32x2 two = {pe0, pe1};
       unsigned pk = __builtin_bit_cast(unsigned, __builtin_convertvector(two, bf16x2));
-      asm volatile("" : "+v"(pk));         // convert here, not where P is consumed an iteration later
+      asm volatile("" : "+v"(pk), "+v"(lsum0), "+v"(lsum1));   // convert here, not where P is consumed
       const bf16x2 b2 = __builtin_bit_cast(bf16x2, pk);
       p_cur[nb][mb][r >> 3][r & 7] = b2[0];
       p_cur[nb][mb][r >> 3][(r & 7) + 1] = b2[1];
     };
+    auto sum_pair = [&](int e) {           // finishes pair e - 2, then pair e's exponentials take its place
+      if (e > 0) finish_pair(e - 2);
+      pe0 = ne0; pe1 = ne1;
+    };
+    // One round = 8 groups, each opened by ONE MFMA: the wave issues in order, and a second MFMA
+    // right behind the first stalls the issue for the 32 cycles the first occupies the pipeline.
     auto round = [&](auto rc_) {
       constexpr int r = decltype(rc_)::value;
+      // the operands of this round went out during the previous one
+      __builtin_amdgcn_s_waitcnt(0xC07F);
+      // groups 0..3: logits of key blocks 0, 1 (k-step r) for query blocks 0, 1
+      if (r == 0) mfma_qk_first(s_nxt[0][0], kf[0][0], qa.q[0][0]);
+      else mfma_qk_acc(s_nxt[0][0], kf[r][0], qa.q[0][r]);
+      exp_pair(8 * r);
       if (r + 1 < 8) {
         kf[(r + 1) & 7][0] = lds_read_k(tK, lo.k[(r + 1) & 7]);
         kf[(r + 1) & 7][1] = lds_read_k(tK, lo.k[(r + 1) & 7] + HALF_BYTES);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (r == 0) mfma_qk_first(s_nxt[0][1], kf[0][0], qa.q[1][0]);
+      else mfma_qk_acc(s_nxt[0][1], kf[r][0], qa.q[1][r]);
+      sum_pair(8 * r);
+      round_dma<r>(kt, vt, k_dst, v_dst);
+      __builtin_amdgcn_sched_barrier(0);
+      if (r == 0) mfma_qk_first(s_nxt[1][0], kf[0][1], qa.q[0][0]);
+      else mfma_qk_acc(s_nxt[1][0], kf[r][1], qa.q[0][r]);
+      exp_pair(8 * r + 2);
+      if (r + 1 < 8) {
         vf[(2 * r + 2) & 15] = fetch_v((2 * r + 2) & 15);
         vf[(2 * r + 3) & 15] = fetch_v((2 * r + 3) & 15);
-        // one wait per round: everything but the 6 reads just issued (this round's operands
-        // went out a round ago); vmcnt and expcnt fields are left open
-        __builtin_amdgcn_s_waitcnt(0xC67F);
-      } else {
-        __builtin_amdgcn_s_waitcnt(0xC07F);
       }
-      round_dma<r>(kt, vt, k_dst, v_dst);
+      __builtin_amdgcn_sched_barrier(0);
+      if (r == 0) mfma_qk_first(s_nxt[1][1], kf[0][1], qa.q[1][0]);
+      else mfma_qk_acc(s_nxt[1][1], kf[r][1], qa.q[1][r]);
+      sum_pair(8 * r + 2);
       if (r == 5) prepare_next();
-      // groups 0, 1: logits of key blocks 0, 1, k-step r
-#pragma unroll
-      for (int mb = 0; mb < 2; ++mb) {
-        if (r == 0) {
-          mfma_qk_first(s_nxt[mb][0], kf[0][mb], qa.q[0][0]);
-          mfma_qk_first(s_nxt[mb][1], kf[0][mb], qa.q[1][0]);
-        } else {
-          mfma_qk_acc(s_nxt[mb][0], kf[r][mb], qa.q[0][r]);
-          mfma_qk_acc(s_nxt[mb][1], kf[r][mb], qa.q[1][r]);
-        }
-        softmax2(8 * r + 2 * mb);
-        asm volatile("" : "+v"(lsum0), "+v"(lsum1));
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      // groups 2, 3: output update steps 2r, 2r + 1 of the previous tile
+      __builtin_amdgcn_sched_barrier(0);
+      // groups 4..7: output update steps 2r, 2r + 1 of the previous tile
 #pragma unroll
       for (int g = 0; g < 2; ++g) {
         const int i = 2 * r + g;
         const int mb = i / 8, tt = (i / 4) & 1, db = i & 3;
         st.o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], p_prev[0][mb][tt], st.o[db][0], 0, 0, 0);
+        exp_pair(8 * r + 4 + 2 * g);
+        __builtin_amdgcn_sched_barrier(0);
         st.o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], p_prev[1][mb][tt], st.o[db][1], 0, 0, 0);
-        softmax2(8 * r + 4 + 2 * g);
-        asm volatile("" : "+v"(lsum0), "+v"(lsum1));
+        sum_pair(8 * r + 4 + 2 * g);
+        if (r == 7 && g == 1) finish_pair(62);
         __builtin_amdgcn_sched_barrier(0);
       }
     };
