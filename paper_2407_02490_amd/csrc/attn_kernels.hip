@@ -663,10 +663,14 @@ struct AshapeCls {
 //    go out one per round (back to back they stall the wave until the memory
 //    pipeline has taken them); scalar bookkeeping sits between the rounds' MFMAs.
 //  - K and V each cycle through three LDS buffers; iteration t issues the loads
-//    of K(t+3) and V(t+1), which have two iterations to land, and reads K(t+1)
-//    and V(t-1).  Slot of tile i: i mod 3.  Past the last tile the loads repeat
-//    it into the free slot, so that every iteration issues 8 loads and one
-//    constant wait count serves.
+//    of K(t+3) and V(t+1) in its rounds 4..7 and reads K(t+1) and V(t-1).  Slot
+//    of tile i: i mod 3.  Past the last tile the loads repeat it into the free
+//    slot, so that every iteration issues 8 loads.
+//  - The one barrier of an iteration sits after round 3 (with a wait for the
+//    loads of the iteration before).  The tiles the next iteration reads are
+//    therefore confirmed half an iteration early, and its first operands are
+//    fetched from LDS in round 7: no LDS latency is exposed at the top of an
+//    iteration and nothing but the loop branch separates two iterations.
 //  - Every wave runs every iteration on every tile of the workgroup's key range,
 //    also on tiles outside its own rows' mask (the four waves meet at a barrier
 //    each iteration, so skipping would only idle): such a tile gets P = 0 via an
@@ -717,14 +721,20 @@ struct AshapeLoop {
     dma_block<ROWS256, I>(d.vw + (size_t)kb * d.v_rb, d.v_rb, d.v_voff[I],
                           lds_addr_of(lds) + 3 * TILE_BYTES + slot_ofs + d.lds_w);
   }
-  template <int R>
-  __device__ inline void round_dma(const char *kt, const char *vt, unsigned k_dst, unsigned v_dst) const {
-    if (R < 4) dma_block<ROWS256, R & 3>(kt, d.k_rb, d.k_voff[R & 3], k_dst);
-    else dma_block<ROWS256, R & 3>(vt, d.v_rb, d.v_voff[R & 3], v_dst);
+  // first operands of an iteration (k-step 0 of both key blocks, output update steps 0, 1): read
+  // during the last round of the iteration before
+  struct Lead {
+    bf16x8 k[2], v[2];
+  };
+  __device__ inline void read_lead(Lead &ld) const {
+    ld.k[0] = lds_read_k(tK_, lo.k[0]);
+    ld.k[1] = lds_read_k(tK_, lo.k[0] + HALF_BYTES);
+    ld.v[0] = lds_read_vt(tV_, lo.v[0][0], lo.v[0][1]);
+    ld.v[1] = lds_read_vt(tV_, lo.v[1][0], lo.v[1][1]);
   }
 
   __device__ inline void iter(int t, f32x16 (&s_cur)[2][2], f32x16 (&s_nxt)[2][2], bf16x8 (&p_prev)[2][2][2],
-                              bf16x8 (&p_cur)[2][2][2]) {
+                              bf16x8 (&p_cur)[2][2][2], Lead &lead) {
     const char *tK = tK_, *tV = tV_;
     auto fetch_v = [&](int i) {            // PV step i = (mb, t, db)
       const int mb = i / 8, tt = (i / 4) & 1, db = i & 3;
@@ -732,10 +742,10 @@ struct AshapeLoop {
       return lds_read_vt(tV, lo.v[db][0] + base, lo.v[db][1] + base);
     };
     bf16x8 kf[8][2], vf[16];
-    kf[0][0] = lds_read_k(tK, lo.k[0]);
-    kf[0][1] = lds_read_k(tK, lo.k[0] + HALF_BYTES);
-    vf[0] = fetch_v(0);
-    vf[1] = fetch_v(1);
+    kf[0][0] = lead.k[0];
+    kf[0][1] = lead.k[1];
+    vf[0] = lead.v[0];
+    vf[1] = lead.v[1];
     // the iteration's scalar operands were prepared during the previous one
     const char *kt = kt_, *vt = vt_;
     const unsigned k_dst = k_dst_, v_dst = v_dst_;
@@ -800,7 +810,7 @@ struct AshapeLoop {
       if (r == 0) mfma_qk_first(s_nxt[0][1], kf[0][0], qa.q[1][0]);
       else mfma_qk_acc(s_nxt[0][1], kf[r][0], qa.q[1][r]);
       sum_pair(8 * r);
-      round_dma<r>(kt, vt, k_dst, v_dst);
+      if (r >= 4) dma_block<ROWS256, r & 3>(kt, d.k_rb, d.k_voff[r & 3], k_dst);
       __builtin_amdgcn_sched_barrier(0);
       if (r == 0) mfma_qk_first(s_nxt[1][0], kf[0][1], qa.q[0][0]);
       else mfma_qk_acc(s_nxt[1][0], kf[r][1], qa.q[0][r]);
@@ -813,6 +823,7 @@ struct AshapeLoop {
       if (r == 0) mfma_qk_first(s_nxt[1][1], kf[0][1], qa.q[1][0]);
       else mfma_qk_acc(s_nxt[1][1], kf[r][1], qa.q[1][r]);
       sum_pair(8 * r + 2);
+      if (r >= 4) dma_block<ROWS256, r & 3>(vt, d.v_rb, d.v_voff[r & 3], v_dst);
       if (r == 5) prepare_next();
       __builtin_amdgcn_sched_barrier(0);
       // groups 4..7: output update steps 2r, 2r + 1 of the previous tile
@@ -826,7 +837,17 @@ struct AshapeLoop {
         st.o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[i], p_prev[1][mb][tt], st.o[db][1], 0, 0, 0);
         sum_pair(8 * r + 4 + 2 * g);
         if (r == 7 && g == 1) finish_pair(62);
+        // the first operands of the next iteration (its tiles were confirmed at this iteration's barrier)
+        if (r == 7 && g == 0) read_lead(lead);
         __builtin_amdgcn_sched_barrier(0);
+      }
+      if (r == 3) {
+        // The iteration's one barrier sits in its middle.  Landed and visible behind it: the loads
+        // issued in rounds 4..7 of the iteration before, K(t+2) and V(t), which the next iteration
+        // reads.  Free behind it: the slots of K(t) and V(t-2), last read in the iteration before,
+        // which this iteration's loads (rounds 4..7) overwrite.
+        MINF_WAIT_VMCNT(0);
+        __syncthreads();
       }
     };
     round(std::integral_constant<int, 0>{});
@@ -847,8 +868,6 @@ struct AshapeLoop {
       has_ref = true;
     }
     cls_cur = cls_nxt;
-    MINF_WAIT_VMCNT(8);     // everything but this iteration's own 8 loads has landed
-    __syncthreads();
   }
 };
 
@@ -890,12 +909,14 @@ __device__ inline void ashape_pass_pipelined(const AshapeCtx &c, const WaveDma &
   }
   __syncthreads();   // all waves are done with K(0) before iteration 0 overwrites it with K(3)
   lp.prepare(0);
+  typename AshapeLoop<ROWS256>::Lead lead;
+  lp.read_lead(lead);
   int t = 0;
   for (; t + 1 <= c.T; t += 2) {
-    lp.iter(t, sa, sb, pa, pb);
-    lp.iter(t + 1, sb, sa, pb, pa);
+    lp.iter(t, sa, sb, pa, pb, lead);
+    lp.iter(t + 1, sb, sa, pb, pa, lead);
   }
-  if (t <= c.T) lp.iter(t, sa, sb, pa, pb);
+  if (t <= c.T) lp.iter(t, sa, sb, pa, pb, lead);
   MINF_WAIT_VMCNT(0);   // the repeated loads of the last iterations
   __syncthreads();
 }
