@@ -2,8 +2,9 @@
 //
 // What is computed: Eq. 1 of the paper, A(M) = softmax(QK^T/sqrt(d) - c(1-M)) V
 // with c -> infinity, for the A-shape, Block-Sparse (App. C.4.1) and
-// Vertical-Slash (App. C.4.2, Alg. 5) masks, with the online-softmax recurrence
-// of Alg. 5 (running max m, running sum l, rescale by exp(m - m_new)).
+// Vertical-Slash (App. C.4.2, Alg. 5) masks; the online-softmax recurrence of
+// Alg. 5 (running max m, running sum l, rescale by exp(m - m_new)) is replaced
+// by a fixed exponent reference with an exact fallback (below).
 //
 // How (differs from the paper's A100/Triton design on purpose):
 //  * One 64-lane wavefront owns one 64-row query block.  Q lives in registers
@@ -32,11 +33,19 @@
 //    If a row sum ends up >= 2^100 or non-finite (logits that outgrow the first
 //    step's max by more than ~69 nats), the whole query block is redone with
 //    the exact two-pass scheme: pass 1 finds every row max, pass 2 accumulates.
+//  * Three tiles in flight per loop iteration: logits of tile t+1, softmax of
+//    tile t, output update of tile t-1.  With one wave per SIMD (the kernels
+//    need about 450 registers) the wave issues one instruction every four
+//    cycles, in order, so the loops are built to an instruction budget: one
+//    MFMA per issue group, logits accumulated in vector registers (reading
+//    accumulator registers queues behind the MFMAs), Q and the LDS operands
+//    in accumulator registers, scalar bookkeeping between MFMAs, constant
+//    wait counts.
 //  * A-shape / dense: a workgroup is 4 waves = 4 consecutive query blocks of
-//    one head; 64-key K/V tiles are staged once in LDS (double buffered) and
-//    shared by the 4 waves.  Block-Sparse / Vertical-Slash: tile lists differ
-//    per query block, so a workgroup is a single wave that streams 32-key
-//    steps through a private double buffer; 4 workgroups share a CU.
+//    one head; 64-key K/V tiles go through three-deep LDS rings shared by the
+//    4 waves.  Block-Sparse / Vertical-Slash: tile lists differ per query
+//    block, so a workgroup is a single wave that streams 32-key steps through
+//    private rings (2 K + 3 V slots, 40 KiB); 4 workgroups share a CU.
 #include <type_traits>
 
 #include "mfma_tile.h"
@@ -521,8 +530,8 @@ __device__ inline void finish_max_pass(WaveState &st, float c_log2) {
 
 // ---------------------------------------------------------------------------
 // A-shape (and dense causal: n_init = 0, n_local >= N).  4 waves, 256 query
-// rows of one head per workgroup; shared, double-buffered 64-key K/V tiles.
-// LDS: 2 stages x (K 16 KiB + V 16 KiB).
+// rows of one head per workgroup; shared 64-key K/V tiles.
+// LDS: 3 K slots + 3 V slots of 16 KiB (the exact fallback pass uses 2 + 2).
 // ---------------------------------------------------------------------------
 struct AshapeCtx {
   const bf16_t *kh, *vh;
@@ -976,10 +985,11 @@ __global__ __launch_bounds__(256) void ashape_kernel(QKV x, HeadList hl, int n_i
 }
 
 // ---------------------------------------------------------------------------
-// Single-wave kernels: 32-key steps through a private double buffer.
-// LDS: 2 stages x (K 8 KiB + V 8 KiB) = 32 KiB (+ column list for VS).
+// Single-wave kernels: 32-key steps through private rings.
+// LDS: 2 K slots + 3 V slots of 8 KiB = 40 KiB (the column list of the
+// Vertical-Slash gather phase lives in the third V slot).
 // One step = 16 global_load_lds instructions (8 K + 8 V); the wave keeps the
-// next step's loads in flight while it computes the current one.
+// next steps' loads in flight while it computes the current one.
 // ---------------------------------------------------------------------------
 // Per-wave LDS ring of the single-wave kernels: K slots 0, 1, then V slots 0, 1, 2 (8 KiB each,
 // 40 KiB: four workgroups fill a CU's 160 KiB).  The two-deep pipelines use V slots 0 and 1.
