@@ -89,6 +89,18 @@ def test_bs_matches_oracle(B, rng):
         assert_close_rows(o[h], want, f"bs head {h}")
 
 
+def test_bs_list_longer_than_one_lane_chunk(B, rng):
+    """More than 64 listed blocks per query block: the list is walked in chunks of 64 ids."""
+    N, topk = 8192, 100
+    NB = N // 64
+    q, k, v = random_qkv(22, 1, 1, N)
+    idx, cnt = random_bs_index(rng, NB, topk)
+    dev = B.bs_index_from_host(idx[None], cnt[None])
+    o = run_heads(B.minf_bs_attn, q, k, v, [0], dev)
+    want = O.bs_attention(to_f64(q[0]), to_f64(k[0]), to_f64(v[0]), idx, cnt)
+    assert_close_rows(o[0], want, "bs topk=100")
+
+
 def test_bs_full_index_is_dense(B):
     N = 512
     NB = N // 64
