@@ -13,6 +13,7 @@ Prints ONE JSON line on stdout; progress goes to stderr.
 """
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -158,7 +159,7 @@ class Layer:
         return r
 
 
-def time_dense(x, heads, reps):
+def time_dense(x, heads, reps, keep=False):
     o = torch.empty_like(x.q)
     B.minf_dense_attn(x.q, x.k, x.v, o, heads[:1])       # touch the code path once, one head
     torch.cuda.synchronize()
@@ -167,8 +168,53 @@ def time_dense(x, heads, reps):
         with t:
             B.minf_dense_attn(x.q, x.k, x.v, o, heads)
     torch.cuda.synchronize()
-    del o
-    return float(np.mean(t.ms()))
+    ms = float(np.mean(t.ms()))
+    return (ms, o) if keep else ms
+
+
+def output_distance(o_sparse, o_dense, heads):
+    """Relative L2 distance of the sparse output from the dense causal one over
+    the given heads -- the quantity the head-pattern search minimises (Alg. 1).
+    Plain reductions over outputs both computed by the library."""
+    num = den = 0.0
+    for h in heads:
+        a, b = o_sparse[h].float(), o_dense[h].float()
+        num += float((a - b).square().sum())
+        den += float(b.square().sum())
+    return round(math.sqrt(num / den), 5) if den > 0 else None
+
+
+def vs_budget_sweep(L, o_dense, reps=3):
+    """Second workload: the Vertical-Slash budgets of W.VS_BUDGET_SWEEP on the
+    inputs of a Vertical-Slash layer; index build and attention timed per call."""
+    x, N = L.x, L.N
+    heads = list(range(L.Hq))
+    dense_tiles = int(C.tiles_dense(N).sum()) * L.Hq
+    out = []
+    for label, nv, ns in W.VS_BUDGET_SWEEP:
+        idx = B.alloc_vs_index(len(heads), nv, ns, N)
+        ws = u8(B.minf_vs_index_workspace_bytes(x.q, x.k, len(heads), L.cfg["last_q"]))
+        ti, ta = Timer(), Timer()
+        for r in range(reps + 1):
+            with ti:
+                B.minf_build_vs_index(x.q, x.k, heads, L.cfg["last_q"], nv, ns, idx, ws)
+            with ta:
+                B.minf_vs_attn(x.q, x.k, x.v, L.o, heads, idx)
+            if r == 0:                      # warm-up
+                torch.cuda.synchronize()
+                ti.reset(); ta.reset()
+        torch.cuda.synchronize()
+        tiles = int(C.vs_index_tiles(idx, N).sum())
+        ms_a = float(np.median(ta.ms()))
+        e = {"setting": label, "nv": nv, "ns": ns, "index_ms": round(float(np.median(ti.ms())), 4),
+             "attn_ms": round(ms_a, 4), "tiles": tiles,
+             "tflops": round(tiles * FT / ms_a / 1e9, 2),
+             "sparsity_vs_causal": round(1.0 - tiles / dense_tiles, 4)}
+        if o_dense is not None:
+            e["output_rel_l2_vs_dense"] = output_distance(L.o, o_dense, heads)
+        out.append(e)
+        del idx, ws
+    return out
 
 
 def cpu_baseline(layer, budget_s=20.0):
@@ -277,12 +323,20 @@ def main():
             wall = L.run(max(a.steps, 3), a.warmup)
             at128[name] = L.report(wall)
             log(name, json.dumps(at128[name]))
-            if name == "c1" and not a.no_dense:
-                ms = time_dense(L.x, list(range(L.Hq)), 2)
-                dt = int(C.tiles_dense(L.N).sum()) * L.Hq
-                at128["dense"] = {"ms": round(ms, 3), "tiles": dt, "tflops": round(dt * FT / ms / 1e9, 2)}
-                log("dense 128K", json.dumps(at128["dense"]))
-            del L
+            o_dense = None
+            if not a.no_dense:
+                # the dense causal output of the same inputs: timed once (on c1's inputs), and the
+                # reference of the output distance of every sparse layer
+                ms, o_dense = time_dense(L.x, list(range(L.Hq)), 2 if name == "c1" else 1, keep=True)
+                if name == "c1":
+                    dt = int(C.tiles_dense(L.N).sum()) * L.Hq
+                    at128["dense"] = {"ms": round(ms, 3), "tiles": dt, "tflops": round(dt * FT / ms / 1e9, 2)}
+                    log("dense 128K", json.dumps(at128["dense"]))
+                at128[name]["output_rel_l2_vs_dense"] = output_distance(L.o, o_dense, list(range(L.Hq)))
+            if name == "c2":
+                at128["c2_budget_sweep"] = vs_budget_sweep(L, o_dense)
+                log("c2 budget sweep", json.dumps(at128["c2_budget_sweep"]))
+            del L, o_dense
             torch.cuda.empty_cache()
         if "dense" in at128:
             for name in ("c1", "c2", "c3"):

@@ -42,9 +42,24 @@ from dataclasses import dataclass, field
 
 import torch
 
-__all__ = ["LayerInputs", "make_layer", "CONFIGS", "make_config", "head_assignment"]
+__all__ = ["LayerInputs", "make_layer", "CONFIGS", "make_config", "head_assignment", "VS_BUDGET_SWEEP"]
 
 BLOCK = 64
+
+# Vertical-Slash budgets (vertical lines, slash lines) of the second workload:
+# the four settings of the head-pattern search space (App. C.2, search-space
+# table), the budget the 128K layer uses, and the two ablation limits that keep
+# one line of the other kind (App. D.3, "only vertical" / "only slash").  They
+# span the column-dominated and the slash-dominated extremes of the sparse kernel.
+VS_BUDGET_SWEEP = [
+    ("search (30, 2048)", 30, 2048),
+    ("search (100, 1800)", 100, 1800),
+    ("search (500, 1500)", 500, 1500),
+    ("search (3000, 200)", 3000, 200),
+    ("default (1000, 6096)", 1000, 6096),
+    ("only vertical (1000, 1)", 1000, 1),
+    ("only slash (1, 6096)", 1, 6096),
+]
 
 
 @dataclass
