@@ -41,8 +41,11 @@ __device__ inline unsigned long long lanes_below(int lane) { return (1ull << lan
 
 // Finds the k-th largest of data[0..n) (1 <= k <= n).  On return *thr is its
 // key and *take_eq the number of elements equal to it that belong to the top-k
-// (to be taken in index order).  hist: 256 ints of LDS, sh: 4 ints of LDS.
-template <int NT>
+// (to be taken in index order).  hist: 256 ints of LDS, sh: 8 ints of LDS.
+// VEC4: data is 16-byte aligned and n a multiple of 4; every thread then has
+// eight elements (two 16-byte loads) in flight per round instead of one, which
+// is what a single workgroup needs to stream a long row from memory.
+template <int NT, bool VEC4>
 __device__ inline void radix_select(const float *data, int n, int k, unsigned *thr, int *take_eq,
                                     int *hist, int *sh) {
   const int tid = threadIdx.x, lane = tid & 63;
@@ -52,15 +55,10 @@ __device__ inline void radix_select(const float *data, int n, int k, unsigned *t
     const int shift = 8 * pass;
     for (int i = tid; i < 256; i += NT) hist[i] = 0;
     __syncthreads();
-    const int n_round = (n + NT - 1) / NT * NT;
-    for (int i = tid; i < n_round; i += NT) {
-      bool part = false;
-      int d = 0;
-      if (i < n) {
-        const unsigned u = order_key(data[i]);
-        part = (u & mask) == prefix;
-        d = (u >> shift) & 255;
-      }
+    // one element per lane, wave-uniform control flow
+    auto tally = [&](bool valid, unsigned u) {
+      const bool part = valid && (u & mask) == prefix;
+      const int d = (u >> shift) & 255;
       // Scores of one row often share their leading byte: add that byte's count
       // once per wave instead of 64 colliding LDS atomics.
       const unsigned long long bal = __builtin_amdgcn_ballot_w64(part);
@@ -70,6 +68,24 @@ __device__ inline void radix_select(const float *data, int n, int k, unsigned *t
         const unsigned long long same = __builtin_amdgcn_ballot_w64(part && d == dl);
         if (lane == lead) atomicAdd(&hist[dl], __builtin_popcountll(same));
         if (part && d != dl) atomicAdd(&hist[d], 1);
+      }
+    };
+    if (VEC4) {
+      const float4 *d4 = reinterpret_cast<const float4 *>(data);
+      const int n4 = n >> 2, n_round = (n4 + 2 * NT - 1) / (2 * NT) * (2 * NT);
+      for (int i = tid; i < n_round; i += 2 * NT) {
+        const bool v0 = i < n4, v1 = i + NT < n4;
+        float4 a = make_float4(0.f, 0.f, 0.f, 0.f), b = a;
+        if (v0) a = d4[i];
+        if (v1) b = d4[i + NT];
+        tally(v0, order_key(a.x)); tally(v0, order_key(a.y)); tally(v0, order_key(a.z)); tally(v0, order_key(a.w));
+        tally(v1, order_key(b.x)); tally(v1, order_key(b.y)); tally(v1, order_key(b.z)); tally(v1, order_key(b.w));
+      }
+    } else {
+      const int n_round = (n + NT - 1) / NT * NT;
+      for (int i = tid; i < n_round; i += NT) {
+        const bool v = i < n;
+        tally(v, v ? order_key(data[i]) : 0u);
       }
     }
     __syncthreads();
@@ -106,22 +122,50 @@ __device__ inline void radix_select(const float *data, int n, int k, unsigned *t
 
 // Writes, ascending, the indices i with key(data[i]) > thr plus the first
 // take_eq indices with key == thr.  Each wave owns a contiguous range; counts
-// are exchanged through sh (2 * NT/64 ints of LDS).
-template <int NT>
+// are exchanged through sh (2 * NT/64 ints of LDS).  VEC4 as above: a lane then
+// holds four consecutive elements per 16-byte load, two loads in flight.
+template <int NT, bool VEC4>
 __device__ inline void ordered_select(const float *data, int n, unsigned thr, int take_eq, int32_t *out,
                                       int *sh) {
   constexpr int NW = NT / 64;
+  constexpr int STEP = VEC4 ? 256 : 64;          // elements a wave takes per load
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int per = ((n + NW - 1) / NW + 63) / 64 * 64;
+  const int per = ((n + NW - 1) / NW + STEP - 1) / STEP * STEP;
   const int lo = min(wave * per, n), hi = min(lo + per, n);
+  // keys of the elements a lane holds at position i0 of the wave's range (0 = below every score)
+  auto load4 = [&](int i0, unsigned (&u)[4]) {
+    const int i = i0 + 4 * lane;
+    u[0] = u[1] = u[2] = u[3] = 0u;
+    if (i < hi) {               // hi, lo and n are multiples of 4
+      const float4 a = *reinterpret_cast<const float4 *>(data + i);
+      u[0] = order_key(a.x); u[1] = order_key(a.y); u[2] = order_key(a.z); u[3] = order_key(a.w);
+    }
+  };
   int gt = 0, eq = 0;
-  for (int i0 = lo; i0 < hi; i0 += 64) {
-    const int i = i0 + lane;
-    unsigned u = 0;
-    const bool in = i < hi;
-    if (in) u = order_key(data[i]);
-    gt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(in && u > thr));
-    eq += __builtin_popcountll(__builtin_amdgcn_ballot_w64(in && u == thr));
+  if (VEC4) {
+    int g = 0, e = 0;
+    for (int i0 = lo; i0 < hi; i0 += 2 * STEP) {
+      unsigned u[4], w[4];
+      load4(i0, u);
+      load4(i0 + STEP, w);
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        g += (u[c] > thr) + (w[c] > thr);
+        e += (u[c] == thr && i0 + 4 * lane < hi) + (w[c] == thr && i0 + STEP + 4 * lane < hi);
+      }
+    }
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) { g += __shfl_xor(g, off); e += __shfl_xor(e, off); }
+    gt = g; eq = e;
+  } else {
+    for (int i0 = lo; i0 < hi; i0 += 64) {
+      const int i = i0 + lane;
+      unsigned u = 0;
+      const bool in = i < hi;
+      if (in) u = order_key(data[i]);
+      gt += __builtin_popcountll(__builtin_amdgcn_ballot_w64(in && u > thr));
+      eq += __builtin_popcountll(__builtin_amdgcn_ballot_w64(in && u == thr));
+    }
   }
   if (lane == 0) { sh[wave] = gt; sh[NW + wave] = eq; }
   __syncthreads();
@@ -131,19 +175,70 @@ __device__ inline void ordered_select(const float *data, int n, unsigned thr, in
     pos += sh[w] + max(0, min(e, take_eq - eq_before));
     eq_before += e;
   }
-  for (int i0 = lo; i0 < hi; i0 += 64) {
-    const int i = i0 + lane;
-    unsigned u = 0;
-    const bool in = i < hi;
-    if (in) u = order_key(data[i]);
-    const bool g = in && u > thr, e = in && u == thr;
-    const unsigned long long eb = __builtin_amdgcn_ballot_w64(e);
-    const int rank = eq_before + __builtin_popcountll(eb & lanes_below(lane));
-    const bool sel = g || (e && rank < take_eq);
-    const unsigned long long sb = __builtin_amdgcn_ballot_w64(sel);
-    if (sel) out[pos + __builtin_popcountll(sb & lanes_below(lane))] = i;
-    pos += __builtin_popcountll(sb);
-    eq_before += __builtin_popcountll(eb);
+  if (VEC4) {
+    // one 256-element group: lane L holds elements 4L .. 4L+3 of it, in index order
+    auto emit = [&](int i0, const unsigned (&u)[4]) {
+      const bool in = i0 + 4 * lane < hi;
+      int ne = 0, ns_ = 0;
+      bool g[4], e[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) { g[c] = u[c] > thr; e[c] = in && u[c] == thr; ne += e[c]; }
+      // equal elements before this lane's, in this group (exclusive lane scan)
+      int e_scan = ne;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(e_scan, off);
+        if (lane >= off) e_scan += o;
+      }
+      const int e_tot = __shfl(e_scan, 63);
+      int rank = eq_before + e_scan - ne;
+      bool sel[4];
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        sel[c] = g[c] || (e[c] && rank < take_eq);
+        rank += e[c];
+        ns_ += sel[c];
+      }
+      int s_scan = ns_;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(s_scan, off);
+        if (lane >= off) s_scan += o;
+      }
+      const int s_tot = __shfl(s_scan, 63);
+      int p = pos + s_scan - ns_;
+#pragma unroll
+      for (int c = 0; c < 4; ++c)
+        if (sel[c]) out[p++] = i0 + 4 * lane + c;
+      pos += s_tot;
+      eq_before += e_tot;
+    };
+    for (int i0 = lo; i0 < hi; i0 += 2 * STEP) {
+      unsigned u[4], w[4];
+      load4(i0, u);
+      load4(i0 + STEP, w);
+      // groups without a kept element (nearly all of a long row) cost two ballots
+      bool any_u = false, any_w = false;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) { any_u |= u[c] >= thr; any_w |= w[c] >= thr; }
+      if (__builtin_amdgcn_ballot_w64(any_u)) emit(i0, u);
+      if (__builtin_amdgcn_ballot_w64(any_w)) emit(i0 + STEP, w);
+    }
+  } else {
+    for (int i0 = lo; i0 < hi; i0 += 64) {
+      const int i = i0 + lane;
+      unsigned u = 0;
+      const bool in = i < hi;
+      if (in) u = order_key(data[i]);
+      const bool g = in && u > thr, e = in && u == thr;
+      const unsigned long long eb = __builtin_amdgcn_ballot_w64(e);
+      const int rank = eq_before + __builtin_popcountll(eb & lanes_below(lane));
+      const bool sel = g || (e && rank < take_eq);
+      const unsigned long long sb = __builtin_amdgcn_ballot_w64(sel);
+      if (sel) out[pos + __builtin_popcountll(sb & lanes_below(lane))] = i;
+      pos += __builtin_popcountll(sb);
+      eq_before += __builtin_popcountll(eb);
+    }
   }
   __syncthreads();
 }
@@ -170,14 +265,15 @@ __device__ inline void ordered_select(const float *data, int n, unsigned thr, in
 // ---------------------------------------------------------------------------
 constexpr int VS_TILE_BYTES = TILE_BYTES;          // 16 KiB
 constexpr int VS_DPAD = 96;                       // slack on both sides of the chunk's diagonal sums
-constexpr int VS_SKEW_PITCH = 128;                // floats per row of the skewed probability tile (32 rows)
+constexpr int VS_SKEW_PITCH = 64;                 // floats per row of the skewed probability tile (32 rows x 32 keys)
 
 template <int PASS>
 __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int last_q, int n_chunks,
                                                       float *ml_part, const float *ml_fin,
                                                       float *colsum, float *diagsum) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  float *dacc = reinterpret_cast<float *>(lds + 2 * VS_TILE_BYTES);   // [VS_DPAD + VS_CHUNK + VS_DPAD], pass 2
+  // pass 1: two 64-key K tiles.  pass 2: two 32-key K half tiles, the diagonal sums, the skewed tile.
+  float *dacc = reinterpret_cast<float *>(lds + 2 * HALF_BYTES);       // [VS_DPAD + VS_CHUNK + VS_DPAD], pass 2
   float *skew = dacc + VS_CHUNK + 2 * VS_DPAD;                         // [32][VS_SKEW_PITCH], pass 2
 
   const int slot = blockIdx.y, chunk = blockIdx.x;
@@ -221,33 +317,32 @@ __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int la
   }
 
   const int key_hi = N - chunk * C;                 // exclusive end of the owned keys
-  const int n_tiles_max = PASS == 1 ? C / 64 : C / 64 + 1;
-  // tiles are 64-aligned: wholly inside [0, N) or outside
-  const int n_tiles = min(n_tiles_max, key_hi / 64);
-  auto tile_key = [&](int mm) { return key_hi - 64 * (mm + 1); };
-  auto fetch = [&](int mm) {
-    dma_rows<1, 64, true>(kh, x.k_st, dl, tile_key(mm), nullptr, N, lds + (mm & 1) * VS_TILE_BYTES, 0, lane);
-  };
-  if (n_tiles > 0) fetch(0);
-  for (int m = 0; m < n_tiles; ++m) {
-    const int kt = tile_key(m);
-    const char *tK = lds + (m & 1) * VS_TILE_BYTES;
-    if (m + 1 < n_tiles) {
-      fetch(m + 1);
-      MINF_WAIT_VMCNT(16);
-    } else {
-      MINF_WAIT_VMCNT(0);
-    }
-    const bool diag_tile = kt + 63 > N - 64;       // only the last 64 keys are cut by causality
-    f32x16 s[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[i][j][r] = 0.f;
 
-    if (PASS == 1) {
+  if (PASS == 1) {
+    // 64-key tiles, two 16 KiB buffers; tiles are 64-aligned: wholly inside [0, N) or outside
+    const int n_tiles = min(C / 64, key_hi / 64);
+    auto tile_key = [&](int mm) { return key_hi - 64 * (mm + 1); };
+    auto fetch = [&](int mm) {
+      dma_rows<1, 64, true>(kh, x.k_st, dl, tile_key(mm), nullptr, N, lds + (mm & 1) * VS_TILE_BYTES, 0, lane);
+    };
+    if (n_tiles > 0) fetch(0);
+    for (int m = 0; m < n_tiles; ++m) {
+      const int kt = tile_key(m);
+      const char *tK = lds + (m & 1) * VS_TILE_BYTES;
+      if (m + 1 < n_tiles) {
+        fetch(m + 1);
+        MINF_WAIT_VMCNT(16);
+      } else {
+        MINF_WAIT_VMCNT(0);
+      }
+      const bool diag_tile = kt + 63 > N - 64;       // only the last 64 keys are cut by causality
+      f32x16 s[2][2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s[i][j][r] = 0.f;
       // s[mb][nb]: register e holds key kt + 32 mb + 16 (e / 8) + 8 h + e % 8, row 32 nb + n
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks)
@@ -286,57 +381,69 @@ __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int la
         l_run = l_run * fast_exp2(m_run - m_use) + sum;
         m_run = m_new;
       }
-    } else {
-      // s[nb][cb]: register r holds row 32 nb + 8 (r / 4) + 4 h + r % 4, key kt + 32 cb + perm_row(n)
+      // the LDS reads of this tile are complete (their data was consumed) before the tile
+      // after next overwrites the buffer: that fetch is issued in the next iteration
+    }
+  } else {
+    // 32-key half tiles, two 8 KiB buffers.  The offsets of the chunk meet the half tiles
+    // 0 .. C/32 + 1; the chunk's own keys are the half tiles 0 .. C/32 - 1.
+    const int n_half = min(C / 32 + 2, key_hi / 32);
+    auto tile_key = [&](int mm) { return key_hi - 32 * (mm + 1); };
+    auto fetch = [&](int mm) {
+      dma_rows<1, 32, true>(kh, x.k_st, dl, tile_key(mm), nullptr, N, lds + (mm & 1) * HALF_BYTES, 0, lane);
+    };
+    // lane (n, h) reads K row n of the half tile: keys run along the lanes in index order
+    int kofs[8];
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks)
+    for (int ks = 0; ks < 8; ++ks) kofs[ks] = swz_byte(n, 2 * ks + h);
+    if (n_half > 0) fetch(0);
+    for (int m = 0; m < n_half; ++m) {
+      const int kt = tile_key(m);
+      const char *tK = lds + (m & 1) * HALF_BYTES;
+      if (m + 1 < n_half) {
+        fetch(m + 1);
+        MINF_WAIT_VMCNT(8);
+      } else {
+        MINF_WAIT_VMCNT(0);
+      }
+      const bool diag_tile = kt + 31 > N - 64;
+      // s[nb]: register r holds row 32 nb + 8 (r / 4) + 4 h + r % 4, key kt + n
+      f32x16 s[2];
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-          const bf16x8 kf = lds_read_k(tK, lo.k[ks] + cb * HALF_BYTES);
-          s[0][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[0][ks], kf, s[0][cb], 0, 0, 0);
-          s[1][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[1][ks], kf, s[1][cb], 0, 0, 0);
-        }
-      const int kcol = perm_row(n);
-      float cs[2] = {0.f, 0.f};
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[j][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 kf = lds_read_k(tK, kofs[ks]);
+        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[0][ks], kf, s[0], 0, 0, 0);
+        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[1][ks], kf, s[1], 0, 0, 0);
+      }
+      float cs = 0.f;
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
-        // rows 32 nb .. 32 nb + 31: local row rl = 8 (r / 4) + 4 h + r % 4, key column kc = 32 cb + kcol;
-        // element (rl, kc) goes to skew[rl][kc - rl + 32]
-        float *wlane = skew + 4 * h * (VS_SKEW_PITCH - 1) + kcol + 32;
+        // rows 32 nb .. 32 nb + 31: local row rl = 8 (r / 4) + 4 h + r % 4, key column n;
+        // element (rl, n) goes to skew[rl][n - rl + 32]
+        float *wlane = skew + 4 * h * (VS_SKEW_PITCH - 1) + n + 32;
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) {
-            const int rl4 = 8 * (r >> 2) + (r & 3);                    // rl - 4 h
-            float pv = fast_exp2(fmaf(s[nb][cb][r], x.c_log2, -off[nb][r]));
-            if (diag_tile) {
-              const int key = kt + 32 * cb + kcol;
-              pv = key <= N - 64 + 32 * nb + rl4 + 4 * h ? pv : 0.f;
-            }
-            cs[cb] += pv;
-            wlane[rl4 * (VS_SKEW_PITCH - 1) + 32 * cb] = pv;
-          }
-        // column j of the skewed tile is the diagonal with local offset 64 m + 32 nb + 32 - j
-        float t1 = 0.f, t2 = 0.f;
-#pragma unroll 8
-        for (int rl = 0; rl < 32; ++rl) {
-          t1 += skew[rl * VS_SKEW_PITCH + lane];
-          t2 += skew[rl * VS_SKEW_PITCH + 64 + lane];
+        for (int r = 0; r < 16; ++r) {
+          const int rl4 = 8 * (r >> 2) + (r & 3);                    // rl - 4 h
+          float pv = fast_exp2(fmaf(s[nb][r], x.c_log2, -off[nb][r]));
+          if (diag_tile) pv = kt + n <= N - 64 + 32 * nb + rl4 + 4 * h ? pv : 0.f;
+          cs += pv;
+          wlane[rl4 * (VS_SKEW_PITCH - 1)] = pv;
         }
-        float *d1 = dacc + VS_DPAD + 64 * m + 32 * nb + 32 - lane;
-        d1[0] += t1;
-        if (lane < 32) d1[-64] += t2;        // columns 96 .. 127 hold no diagonal
+        // column j of the skewed tile is the diagonal with local offset 32 (m + nb) - j
+        float t = 0.f;
+#pragma unroll 8
+        for (int rl = 0; rl < 32; ++rl) t += skew[rl * VS_SKEW_PITCH + lane];
+        dacc[VS_DPAD + 32 * (m + nb) - lane] += t;
       }
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb) {
-        // the two lane halves hold the two halves of the rows of the same keys
-        const float other = __shfl_xor(cs[cb], 32);
-        const float tot = h == 0 ? cs[cb] + other : other + cs[cb];   // same operand order in both
-        if (h == 0 && m < C / 64) colsum[(int64_t)slot * N + kt + 32 * cb + kcol] = tot;
-      }
+      // the two lane halves hold the two halves of the rows of the same key
+      const float other = __shfl_xor(cs, 32);
+      const float tot = h == 0 ? cs + other : other + cs;   // same operand order in both
+      if (h == 0 && m < C / 32) colsum[(int64_t)slot * N + kt + n] = tot;
     }
-    // the LDS reads of this tile are complete (their data was consumed) before the tile
-    // after next overwrites the buffer: that fetch is issued in the next iteration
   }
 
   if (PASS == 1) {
@@ -365,18 +472,41 @@ __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int la
   }
 }
 
-// Combine the per-chunk (max, sum) pairs of every estimating row, in chunk
-// order, into (row max, 1 / row sum).
-__global__ __launch_bounds__(64) void vs_combine_kernel(int n_chunks, const float *ml_part, float *ml_fin) {
-  const int slot = blockIdx.x, r = threadIdx.x;
-  const float *src = ml_part + (int64_t)slot * n_chunks * 128;
+// Combine the per-chunk (max, sum) pairs of every estimating row into (row max,
+// 1 / row sum).  16 waves per head: wave g reduces a contiguous range of chunks
+// in chunk order, the 16 partial results are then combined in wave order, so the
+// result does not depend on timing.
+__global__ __launch_bounds__(1024) void vs_combine_kernel(int n_chunks, const float *ml_part, float *ml_fin) {
+  __shared__ float red[16][64];
+  const int slot = blockIdx.x, r = threadIdx.x & 63, g = threadIdx.x >> 6;
+  const float2 *src = reinterpret_cast<const float2 *>(ml_part) + (int64_t)slot * n_chunks * 64 + r;
+  const int per = (n_chunks + 15) / 16, c0 = min(g * per, n_chunks), c1 = min(c0 + per, n_chunks);
   float M = -INFINITY;
-  for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, src[(c * 64 + r) * 2]);
+#pragma unroll 8
+  for (int c = c0; c < c1; ++c) M = fmaxf(M, src[c * 64].x);
+  red[g][r] = M;
+  __syncthreads();
+  M = red[0][r];
+#pragma unroll
+  for (int i = 1; i < 16; ++i) M = fmaxf(M, red[i][r]);
+  __syncthreads();
   float L = 0.f;
-  if (M != -INFINITY)
-    for (int c = 0; c < n_chunks; ++c) L += src[(c * 64 + r) * 2 + 1] * fast_exp2(src[(c * 64 + r) * 2] - M);
-  ml_fin[(slot * 64 + r) * 2 + 0] = M == -INFINITY ? 0.f : M;
-  ml_fin[(slot * 64 + r) * 2 + 1] = L > 0.f ? 1.0f / L : 0.f;
+  if (M != -INFINITY) {
+#pragma unroll 8
+    for (int c = c0; c < c1; ++c) {
+      const float2 ml = src[c * 64];
+      L += ml.y * fast_exp2(ml.x - M);
+    }
+  }
+  red[g][r] = L;
+  __syncthreads();
+  if (g == 0) {
+    L = red[0][r];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) L += red[i][r];
+    ml_fin[(slot * 64 + r) * 2 + 0] = M == -INFINITY ? 0.f : M;
+    ml_fin[(slot * 64 + r) * 2 + 1] = L > 0.f ? 1.0f / L : 0.f;
+  }
 }
 
 // Top-k + "sparseformat".  blockIdx.y = 0: verticals from the column sums;
@@ -395,8 +525,8 @@ __global__ __launch_bounds__(1024) void vs_select_kernel(int N, int nv, int ns, 
   int32_t *out = which == 0 ? v_idx + (int64_t)slot * nv : s_idx + (int64_t)slot * ns;
   unsigned thr;
   int take_eq;
-  radix_select<1024>(data, N, k, &thr, &take_eq, hist, sh);
-  ordered_select<1024>(data, N, thr, take_eq, out, sh + 8);
+  radix_select<1024, true>(data, N, k, &thr, &take_eq, hist, sh);      // N % 64 == 0, rows 256-byte aligned
+  ordered_select<1024, true>(data, N, thr, take_eq, out, sh + 8);
   for (int i = k + tid; i < kcap; i += 1024) out[i] = 0;
   if (which == 0) {
     if (tid == 0) counts[slot * 4 + 0] = k;
@@ -564,8 +694,8 @@ __global__ __launch_bounds__(256) void bs_select_kernel(int NB, int slot0, int t
   } else {
     unsigned thr;
     int take_eq;
-    radix_select<256>(row, n, k, &thr, &take_eq, hist, sh);
-    ordered_select<256>(row, n, thr, take_eq, out, sh + 8);
+    radix_select<256, false>(row, n, k, &thr, &take_eq, hist, sh);
+    ordered_select<256, false>(row, n, thr, take_eq, out, sh + 8);
   }
   if (tid == 0) blk_cnt[(int64_t)slot * NB + b] = k;
 }
@@ -594,19 +724,14 @@ hipError_t launch_build_vs(const QKV &x, const HeadList &hl, int last_q, int nv,
   float *diagsum = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * N * sizeof(float));
   float *ml_part = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * nc * 128 * sizeof(float));
   float *ml_fin = reinterpret_cast<float *>(p);
-  const size_t lds = 2 * VS_TILE_BYTES + (VS_CHUNK + 2 * VS_DPAD + 32 * VS_SKEW_PITCH) * sizeof(float);
-  hipError_t e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void *>(vs_score_kernel<1>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void *>(vs_score_kernel<2>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  if (e != hipSuccess) return e;
+  // 32 KiB and 29 KiB per one-wave workgroup: five workgroups per CU
+  const size_t lds1 = 2 * VS_TILE_BYTES;
+  const size_t lds2 = 2 * HALF_BYTES + (VS_CHUNK + 2 * VS_DPAD + 32 * VS_SKEW_PITCH) * sizeof(float);
   const dim3 grid(nc, hl.n);
-  hipLaunchKernelGGL(vs_score_kernel<1>, grid, dim3(64), lds, st, x, hl, last_q, nc, ml_part,
+  hipLaunchKernelGGL(vs_score_kernel<1>, grid, dim3(64), lds1, st, x, hl, last_q, nc, ml_part,
                      (const float *)nullptr, (float *)nullptr, (float *)nullptr);
-  hipLaunchKernelGGL(vs_combine_kernel, dim3(hl.n), dim3(64), 0, st, nc, (const float *)ml_part, ml_fin);
-  hipLaunchKernelGGL(vs_score_kernel<2>, grid, dim3(64), lds, st, x, hl, last_q, nc, (float *)nullptr,
+  hipLaunchKernelGGL(vs_combine_kernel, dim3(hl.n), dim3(1024), 0, st, nc, (const float *)ml_part, ml_fin);
+  hipLaunchKernelGGL(vs_score_kernel<2>, grid, dim3(64), lds2, st, x, hl, last_q, nc, (float *)nullptr,
                      (const float *)ml_fin, colsum, diagsum);
   hipLaunchKernelGGL(vs_select_kernel, dim3(hl.n, 2), dim3(1024), 0, st, N, nv, ns, (const float *)colsum,
                      (const float *)diagsum, v_idx, s_idx, cover, cover_bits, counts, cover_words);
