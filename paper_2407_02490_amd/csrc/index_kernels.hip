@@ -243,6 +243,74 @@ __device__ inline void ordered_select(const float *data, int n, unsigned thr, in
   __syncthreads();
 }
 
+// k-th largest of n order keys held in LDS (1 <= k <= n); same contract as
+// radix_select.  Meant for short lists: one key per thread and round.
+template <int NT>
+__device__ inline void radix_select_lds(const unsigned *keys, int n, int k, unsigned *thr, int *take_eq,
+                                        int *hist, int *sh) {
+  const int tid = threadIdx.x, lane = tid & 63;
+  unsigned prefix = 0, mask = 0;
+  int krem = k;
+  for (int pass = 3; pass >= 0; --pass) {
+    const int shift = 8 * pass;
+    for (int i = tid; i < 256; i += NT) hist[i] = 0;
+    __syncthreads();
+    for (int i = tid; i < n; i += NT) {
+      const unsigned u = keys[i];
+      if ((u & mask) == prefix) atomicAdd(&hist[(u >> shift) & 255], 1);
+    }
+    __syncthreads();
+    int suf = 0, own = 0;
+    if (tid < 256) {
+      own = hist[tid];
+      suf = own;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_down(suf, off);
+        if (lane + off < 64) suf += o;
+      }
+      if (lane == 0) sh[tid >> 6] = suf;
+    }
+    __syncthreads();
+    if (tid < 256) {
+      for (int w = (tid >> 6) + 1; w < 4; ++w) suf += sh[w];
+      if (suf >= krem && suf - own < krem) {
+        sh[4] = tid;
+        sh[5] = krem - (suf - own);
+      }
+    }
+    __syncthreads();
+    prefix |= (unsigned)sh[4] << shift;
+    mask |= 255u << shift;
+    krem = sh[5];
+    __syncthreads();
+  }
+  *thr = prefix;
+  *take_eq = krem;
+}
+
+// Exclusive prefix sums of two counters over the 256 threads of a workgroup, in
+// thread order; *ta, *tb receive the totals.  sh: 8 ints of LDS.
+__device__ inline void block_scan2_256(int a, int b, int *ea, int *eb, int *ta, int *tb, int *sh) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int ia = a, ib = b;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int oa = __shfl_up(ia, off), ob = __shfl_up(ib, off);
+    if (lane >= off) { ia += oa; ib += ob; }
+  }
+  if (lane == 63) { sh[wave] = ia; sh[4 + wave] = ib; }
+  __syncthreads();
+  int ba = 0, bb = 0, sa = 0, sb = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    if (w < wave) { ba += sh[w]; bb += sh[4 + w]; }
+    sa += sh[w]; sb += sh[4 + w];
+  }
+  __syncthreads();
+  *ea = ba + ia - a; *eb = bb + ib - b; *ta = sa; *tb = sb;
+}
+
 // ---------------------------------------------------------------------------
 // Vertical-Slash score kernels.  Estimating row r (0..63) is query N-64+r; rows
 // r < 64 - last_q do not take part.  Workgroup (head slot, chunk c), one wave,
@@ -680,24 +748,120 @@ __global__ __launch_bounds__(64) void bs_logits_kernel(int NB, int slot0, KvMap 
       }
 }
 
-// grid (NB, heads of the batch): row b keeps its min(topk, b+1) largest logits among c <= b
+// grid (NB, heads of the batch): row b keeps its min(topk, b+1) largest logits among c <= b.
+// Rows of up to 256 * BS_SEL_E logits are read once, 16 bytes per load, and held in registers
+// (thread t: elements 4 t .. 4 t + 3, 1024 + 4 t .. and so on; needs NB % 4 == 0).  The k-th largest of the 256 thread maxima is a lower bound of the k-th
+// largest logit (k <= 256 maxima are at least that large), so only the logits that reach it
+// -- a few hundred of a long row -- go to LDS as candidates; the exact threshold is found among
+// them, the kept positions are marked in two bit maps (above the threshold / equal to it) and
+// written out in index order, equal logits lowest index first.  Rows that do not fit (longer
+// rows, k > 256, more candidates than LDS holds, e.g. a constant row) take the general
+// radix select over memory.
+constexpr int BS_SEL_E = 64;
+constexpr int BS_SEL_CAP = 2048;
 __global__ __launch_bounds__(256) void bs_select_kernel(int NB, int slot0, int topk, const float *scores,
                                                         int32_t *blk_idx, int32_t *blk_cnt) {
   __shared__ int hist[256];
   __shared__ int sh[24];
+  __shared__ unsigned ckey[BS_SEL_CAP];
+  __shared__ int cidx[BS_SEL_CAP];
+  __shared__ unsigned bitg[256 * BS_SEL_E / 32], bite[256 * BS_SEL_E / 32];
   const int b = blockIdx.x, hb = blockIdx.y, slot = slot0 + hb, tid = threadIdx.x;
   const float *row = scores + ((int64_t)hb * NB + b) * NB;
   int32_t *out = blk_idx + ((int64_t)slot * NB + b) * topk;
   const int n = b + 1, k = min(topk, n);
+  if (tid == 0) blk_cnt[(int64_t)slot * NB + b] = k;
   if (n <= topk) {
     for (int i = tid; i < topk; i += 256) out[i] = i < n ? i : -1;
-  } else {
-    unsigned thr;
-    int take_eq;
-    radix_select<256, false>(row, n, k, &thr, &take_eq, hist, sh);
-    ordered_select<256, false>(row, n, thr, take_eq, out, sh + 8);
+    return;
   }
-  if (tid == 0) blk_cnt[(int64_t)slot * NB + b] = k;
+  bool general = k > 256 || n > 256 * BS_SEL_E || (NB & 3) != 0;
+  if (!general) {
+    unsigned u[BS_SEL_E];
+    unsigned mx = 0u;
+#pragma unroll
+    for (int j = 0; j < BS_SEL_E / 4; ++j) {
+      u[4 * j] = u[4 * j + 1] = u[4 * j + 2] = u[4 * j + 3] = 0u;
+      if (j * 1024 < n) {                     // wave-uniform
+        const int i = j * 1024 + 4 * tid;
+        if (i < n) {                          // the row's storage extends to NB >= i + 4
+          const float4 a = *reinterpret_cast<const float4 *>(row + i);
+          u[4 * j] = max(order_key(a.x), 1u);            // 0 marks "no element"
+          if (i + 1 < n) u[4 * j + 1] = max(order_key(a.y), 1u);
+          if (i + 2 < n) u[4 * j + 2] = max(order_key(a.z), 1u);
+          if (i + 3 < n) u[4 * j + 3] = max(order_key(a.w), 1u);
+        }
+        mx = max(max(mx, u[4 * j]), max(u[4 * j + 1], max(u[4 * j + 2], u[4 * j + 3])));
+      }
+    }
+    ckey[tid] = mx;
+    __syncthreads();
+    unsigned bound;
+    int unused;
+    radix_select_lds<256>(ckey, 256, k, &bound, &unused, hist, sh);
+    bound = max(bound, 1u);
+    int cnt = 0;
+#pragma unroll
+    for (int j = 0; j < BS_SEL_E; ++j)
+      if ((j >> 2) * 1024 < n) cnt += u[j] >= bound;
+    int base, e0, total, t1;
+    block_scan2_256(cnt, 0, &base, &e0, &total, &t1, sh);
+    general = total > BS_SEL_CAP;             // uniform over the workgroup
+    if (!general) {
+#pragma unroll
+      for (int j = 0; j < BS_SEL_E; ++j)
+        if ((j >> 2) * 1024 < n && u[j] >= bound) {
+          ckey[base] = u[j];
+          cidx[base] = (j >> 2) * 1024 + 4 * tid + (j & 3);
+          ++base;
+        }
+      const int nw = (n + 31) >> 5;
+      for (int w = tid; w < nw; w += 256) { bitg[w] = 0u; bite[w] = 0u; }
+      __syncthreads();
+      unsigned thr;
+      int take_eq;
+      radix_select_lds<256>(ckey, total, k, &thr, &take_eq, hist, sh);
+      for (int c = tid; c < total; c += 256) {
+        const unsigned key = ckey[c];
+        const int i = cidx[c];
+        if (key > thr) atomicOr(&bitg[i >> 5], 1u << (i & 31));
+        else if (key == thr) atomicOr(&bite[i >> 5], 1u << (i & 31));
+      }
+      __syncthreads();
+      // thread t owns the words 2t, 2t + 1 (positions 64 t .. 64 t + 63)
+      unsigned G[2], E[2];
+#pragma unroll
+      for (int w = 0; w < 2; ++w) {
+        const bool in = 2 * tid + w < nw;
+        G[w] = in ? bitg[2 * tid + w] : 0u;
+        E[w] = in ? bite[2 * tid + w] : 0u;
+      }
+      int gb, eb, tg, te;
+      block_scan2_256(__builtin_popcount(G[0]) + __builtin_popcount(G[1]),
+                      __builtin_popcount(E[0]) + __builtin_popcount(E[1]), &gb, &eb, &tg, &te, sh);
+#pragma unroll
+      for (int w = 0; w < 2; ++w) {
+        unsigned m = G[w] | E[w];
+        while (m) {
+          const int bit = __builtin_ctz(m);
+          m &= m - 1u;
+          const int i = 64 * tid + 32 * w + bit;
+          if ((G[w] >> bit) & 1u) {
+            out[gb + min(eb, take_eq)] = i;
+            ++gb;
+          } else {
+            if (eb < take_eq) out[gb + eb] = i;
+            ++eb;
+          }
+        }
+      }
+      return;
+    }
+  }
+  unsigned thr;
+  int take_eq;
+  radix_select<256, false>(row, n, k, &thr, &take_eq, hist, sh);
+  ordered_select<256, false>(row, n, thr, take_eq, out, sh + 8);
 }
 
 // ---------------------------------------------------------------------------

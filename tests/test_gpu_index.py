@@ -126,6 +126,31 @@ def test_bs_index_random_inputs(B, N, topk):
         check_bs_index(idx, r, to_f64(q[h]), to_f64(k[h // 2]), topk)
 
 
+@pytest.mark.parametrize("NB,topk", [(64, 7), (2304, 100)])
+def test_bs_index_equal_logits_keep_the_lowest_blocks(B, NB, topk):
+    """Every key block is the same 64 rows, so all logits of a row are exactly equal:
+    the kept blocks are the first min(topk, b+1) ones.  NB = 2304 has rows with more
+    equal candidates than the selection kernel stages on chip (its general path)."""
+    N = 64 * NB
+    g = torch.Generator().manual_seed(21)
+    q = torch.randn(1, N, 128, generator=g).to(torch.bfloat16).cuda()
+    k = torch.randn(1, 64, 128, generator=g).to(torch.bfloat16).repeat(1, NB, 1).cuda()
+    idx = build_bs(B, q, k, [0], topk)
+    got = idx.blk_idx[0].cpu().numpy()
+    cnt = idx.blk_cnt[0].cpu().numpy()
+    want_cnt = np.minimum(topk, np.arange(NB) + 1)
+    assert np.array_equal(cnt, want_cnt)
+    want = np.where(np.arange(topk)[None, :] < want_cnt[:, None], np.arange(topk)[None, :], -1)
+    assert np.array_equal(got, want)
+
+
+def test_bs_index_budget_above_256_blocks(B):
+    """A budget larger than the number of threads of the selection workgroup."""
+    q, k, v = random_qkv(15, 2, 1, 64 * 400)
+    idx = build_bs(B, q, k, [1], 300)
+    check_bs_index(idx, 0, to_f64(q[1]), to_f64(k[0]), 300)
+
+
 def test_bs_clustered_layer_end_to_end(B):
     """Workload c3's recipe at a reduced length: index build + attention."""
     x = W.make_config("c3", N=8192, n_q_heads=4, n_kv_heads=2)
