@@ -1893,7 +1893,7 @@ static hipError_t set_lds(const void *fn, size_t bytes) {
 
 hipError_t launch_ashape(const QKV &x, const HeadList &hl, int n_init, int n_local, hipStream_t st) {
   const int NB = x.N / BQ, NSB = (NB + 3) / 4;
-  const Sched s = make_sched(hl.n, NSB);
+  const Sched s = make_sched(hl, x.group, NSB);
   const size_t lds = 6 * TILE_BYTES;   // three K and three V buffers
   // rows 256 bytes apart in both K and V (the [head][token][128] layout): cheaper tile fetch
   const bool rows256 = x.k_st == D && x.v_st == D;
@@ -1911,7 +1911,7 @@ hipError_t launch_ashape(const QKV &x, const HeadList &hl, int n_init, int n_loc
 hipError_t launch_bs(const QKV &x, const HeadList &hl, const int32_t *blk_idx, const int32_t *blk_cnt,
                      int topk, hipStream_t st) {
   const int NB = x.N / BQ;
-  const Sched s = make_sched(hl.n, NB);
+  const Sched s = make_sched(hl, x.group, NB);
   const size_t lds = 5 * HALF_BYTES;
   const bool rows256 = x.k_st == D && x.v_st == D;
   const void *fn = rows256 ? reinterpret_cast<const void *>(bs_kernel<true>)
@@ -1929,7 +1929,7 @@ hipError_t launch_vs(const QKV &x, const HeadList &hl, const int32_t *v_idx, con
                      const uint32_t *cover_bits, const int32_t *counts, int nv, int ns,
                      int cover_words, hipStream_t st) {
   const int NB = x.N / BQ;
-  const Sched s = make_sched(hl.n, NB);
+  const Sched s = make_sched(hl, x.group, NB);
   const size_t lds = 5 * HALF_BYTES;
   // gathered rows are addressed with 32-bit byte offsets from the head base
   if ((uint64_t)x.N * (uint64_t)x.k_st * 2u >= (1ull << 32) || (uint64_t)x.N * (uint64_t)x.v_st * 2u >= (1ull << 32))
