@@ -200,3 +200,49 @@ def test_index_builders_token_major_layout(B):
     bidx = build_bs(B, q, k, heads, 8)
     for r, h in enumerate(heads):
         check_bs_index(bidx, r, to_f64(q0[h]), to_f64(k0[h // 2]), 8)
+
+
+def test_batch_of_two_all_calls(B):
+    """[batch, heads, N, d] tensors: every entry point loops over the batch; index rows are
+    batch-major (row = batch index * n_heads + position in the head list)."""
+    N, nb = 1024, 2
+    g = torch.Generator().manual_seed(31)
+    q = torch.randn(nb, 4, N, 128, generator=g).to(torch.bfloat16).cuda()
+    k = torch.randn(nb, 2, N, 128, generator=g).to(torch.bfloat16).cuda()
+    v = torch.randn(nb, 2, N, 128, generator=g).to(torch.bfloat16).cuda()
+    heads = [1, 2]
+    # Vertical-Slash
+    nv, ns = 20, 40
+    idx = B.alloc_vs_index(nb * len(heads), nv, ns, N)
+    ws = torch.empty(B.minf_vs_index_workspace_bytes(q, k, len(heads), 64), dtype=torch.uint8, device="cuda")
+    B.minf_build_vs_index(q, k, heads, 64, nv, ns, idx, ws)
+    o = torch.full_like(q, float("nan"))
+    B.minf_vs_attn(q, k, v, o, heads, idx)
+    torch.cuda.synchronize()
+    for b in range(nb):
+        for j, h in enumerate(heads):
+            Qh, Kh, Vh = to_f64(q[b, h]), to_f64(k[b, h // 2]), to_f64(v[b, h // 2])
+            Vg, Sg, _ = check_vs_index(idx, b * len(heads) + j, N, Qh, Kh, 64, nv, ns)
+            assert_close_rows(o[b, h], O.vs_attention(Qh, Kh, Vh, Vg, Sg), f"batch {b} vs head {h}")
+        assert torch.isnan(o[b, 0].float()).all() and torch.isnan(o[b, 3].float()).all()   # heads not named stay untouched
+    # Block-Sparse
+    topk = 5
+    bidx = B.alloc_bs_index(nb * len(heads), N, topk)
+    ws = torch.empty(B.minf_bs_index_workspace_bytes(q, k, len(heads)), dtype=torch.uint8, device="cuda")
+    B.minf_build_bs_index(q, k, heads, topk, bidx, ws)
+    o = torch.full_like(q, float("nan"))
+    B.minf_bs_attn(q, k, v, o, heads, bidx)
+    torch.cuda.synchronize()
+    for b in range(nb):
+        for j, h in enumerate(heads):
+            Qh, Kh, Vh = to_f64(q[b, h]), to_f64(k[b, h // 2]), to_f64(v[b, h // 2])
+            got, cnt, _ = check_bs_index(bidx, b * len(heads) + j, Qh, Kh, topk)
+            assert_close_rows(o[b, h], O.bs_attention(Qh, Kh, Vh, got, cnt), f"batch {b} bs head {h}")
+    # A-shape and dense
+    o = torch.full_like(q, float("nan"))
+    B.minf_ashape_attn(q, k, v, o, [0], 64, 200)
+    B.minf_dense_attn(q, k, v, o, [3])
+    torch.cuda.synchronize()
+    for b in range(nb):
+        assert_close_rows(o[b, 0], O.ashape_attention(to_f64(q[b, 0]), to_f64(k[b, 0]), to_f64(v[b, 0]), 64, 200), f"batch {b} a-shape")
+        assert_close_rows(o[b, 3], O.dense_attention(to_f64(q[b, 3]), to_f64(k[b, 1]), to_f64(v[b, 1])), f"batch {b} dense")
