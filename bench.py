@@ -217,6 +217,41 @@ def vs_budget_sweep(L, o_dense, reps=3):
     return out
 
 
+def short_context(lengths=(8192, 16384, 32768, 65536), reps=5):
+    """Short prompts (App. D.2: below some length the index build is a large share of the
+    time and sparse attention no faster than dense): the Vertical-Slash layer recipe at
+    reduced lengths, default budgets; index, sparse attention and our dense kernel timed
+    per call, all 32 heads."""
+    out = []
+    c = W.CONFIGS["c2"]
+    for N in lengths:
+        x = W.make_config("c2", device="cuda", N=N)
+        heads = list(range(x.n_q_heads))
+        o = torch.empty_like(x.q)
+        idx = B.alloc_vs_index(len(heads), c["nv"], c["ns"], N)
+        ws = u8(B.minf_vs_index_workspace_bytes(x.q, x.k, len(heads), c["last_q"]))
+        ti, ta, td = Timer(), Timer(), Timer()
+        for r in range(reps + 1):
+            with ti:
+                B.minf_build_vs_index(x.q, x.k, heads, c["last_q"], c["nv"], c["ns"], idx, ws)
+            with ta:
+                B.minf_vs_attn(x.q, x.k, x.v, o, heads, idx)
+            with td:
+                B.minf_dense_attn(x.q, x.k, x.v, o, heads)
+            if r == 0:
+                torch.cuda.synchronize()
+                ti.reset(); ta.reset(); td.reset()
+        torch.cuda.synchronize()
+        mi, ma, md = (float(np.median(t.ms())) for t in (ti, ta, td))
+        tiles = int(C.vs_index_tiles(idx, N).sum())
+        out.append({"seq_len": N, "vs_index_ms": round(mi, 4), "vs_attn_ms": round(ma, 4), "dense_ms": round(md, 4),
+                    "index_share": round(mi / (mi + ma), 3), "speedup_vs_our_dense": round(md / (mi + ma), 2),
+                    "sparsity_vs_causal": round(1.0 - tiles / (int(C.tiles_dense(N).sum()) * len(heads)), 4)})
+        del x, o, idx, ws
+        torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(layer, budget_s=20.0):
     """The CPU oracle, as it stands, on a bounded sample of the workload:
     one Vertical-Slash head's index build in full, then attention on sampled
@@ -342,6 +377,8 @@ def main():
             for name in ("c1", "c2", "c3"):
                 at128[name]["speedup_vs_our_dense"] = round(at128["dense"]["ms"] / at128[name]["ms_per_layer"], 2)
         extra["at_128k"] = at128
+        extra["short_context"] = short_context()
+        log("short context", json.dumps(extra["short_context"]))
 
     # ---- the timed workload
     L = Layer(a.workload)

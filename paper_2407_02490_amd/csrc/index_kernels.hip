@@ -630,18 +630,26 @@ __global__ __launch_bounds__(1024) void vs_select_kernel(int N, int nv, int ns, 
     const int rid = before + __builtin_popcountll(sb & lanes_below(lane)) + (start ? 1 : 0) - 1;
     if (start) runs[rid].x = o - 63;
     if (last) runs[rid].y = o + 1;
-    if (i < k) {
-      // offsets o-63 .. o  ->  bits o+1 .. o+64
-      const int b0 = o + 1, b1 = o + 64;
-      const int w0 = b0 >> 5, w1 = b1 >> 5;
-      for (int w = w0; w <= w1; ++w) {
-        const int lo = max(b0, w * 32) - w * 32, hi = min(b1, w * 32 + 31) - w * 32;
-        const unsigned msk = (hi == 31 ? 0xffffffffu : ((1u << (hi + 1)) - 1u)) & ~((1u << lo) - 1u);
-        atomicOr(&bits[w], msk);
-      }
-    }
     run_base += total;
     __syncthreads();
+  }
+  // ---- run bitmap: run [t0, t1) sets the bits t0 + 64 .. t1 + 63, one wave per run, one lane per
+  // word.  Runs are disjoint, so only the first and the last word of a run can be shared with a
+  // neighbour and need an atomic; the words in between are whole.  (One atomic per kept offset
+  // and word, as a first version had it, makes thousands of atomics meet on the same few words.)
+  __threadfence_block();
+  __syncthreads();
+  for (int r = wave; r < run_base; r += 16) {
+    const int2 rr = runs[r];
+    const int b0 = rr.x + 64, b1 = rr.y + 63;          // inclusive bit range
+    const int w0 = b0 >> 5, w1 = b1 >> 5;
+    for (int w = w0 + lane; w <= w1; w += 64) {
+      unsigned m = 0xffffffffu;
+      if (w == w0) m &= ~((1u << (b0 & 31)) - 1u);
+      if (w == w1 && (b1 & 31) != 31) m &= (1u << ((b1 & 31) + 1)) - 1u;
+      if (w == w0 || w == w1) atomicOr(&bits[w], m);
+      else bits[w] = m;
+    }
   }
   if (tid == 0) {
     counts[slot * 4 + 1] = k;
