@@ -38,6 +38,31 @@ def test_dense_matches_oracle(B, N, nq, nkv):
         assert_close_rows(o[h], want, f"dense N={N} head {h}")
 
 
+@pytest.mark.parametrize("heads", [[0, 1, 2, 3, 4, 5, 6, 7, 8], [5, 1, 12, 3], [9, 10, 11, 15, 2, 3],
+                                   list(range(16))])
+def test_head_lists_of_mixed_kv_groups(B, rng, heads):
+    """Work items are scheduled in chunks of consecutive list entries that share a K/V head
+    (here 8 query heads per K/V head): full and partial groups, a group longer than one chunk
+    would be, unsorted lists.  Every listed (head, block) must be computed exactly once, by
+    all three kernels' mappings, and no other head touched."""
+    N, nq, nkv = 704, 16, 2            # 11 blocks
+    q, k, v = random_qkv(5, nq, nkv, N)
+    NB = N // 64
+    o = run_heads(B.minf_dense_attn, q, k, v, heads)
+    idxs = [random_bs_index(rng, NB, 3) for _ in heads]
+    dev = B.bs_index_from_host(np.stack([i for i, _ in idxs]), np.stack([c for _, c in idxs]))
+    ob = run_heads(B.minf_bs_attn, q, k, v, heads, dev)
+    Vl, Sl = [0, 100, 333], [0, 1, 200]
+    ov = run_heads(B.minf_vs_attn, q, k, v, heads, B.vs_index_from_host([Vl] * len(heads), [Sl] * len(heads), N))
+    for r, h in enumerate(heads):
+        Qh, Kh, Vh = to_f64(q[h]), to_f64(k[h // 8]), to_f64(v[h // 8])
+        assert_close_rows(o[h], O.dense_attention(Qh, Kh, Vh), f"dense head {h}")
+        assert_close_rows(ob[h], O.bs_attention(Qh, Kh, Vh, idxs[r][0], idxs[r][1]), f"bs head {h}")
+        assert_close_rows(ov[h], O.vs_attention(Qh, Kh, Vh, Vl, Sl, Bm=64), f"vs head {h}")
+    for h in set(range(nq)) - set(heads):
+        assert torch.isnan(o[h].float()).all() and torch.isnan(ob[h].float()).all() and torch.isnan(ov[h].float()).all()
+
+
 @pytest.mark.parametrize("n_init,n_local", [(64, 128), (100, 200), (0, 65), (5, 1), (1024, 4096), (130, 64)])
 def test_ashape_matches_oracle(B, n_init, n_local):
     N, nq, nkv = 1344, 4, 2          # 21 blocks: last workgroup has one idle wave slot
