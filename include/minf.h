@@ -93,10 +93,21 @@ typedef struct {
  *   blk_idx [rows, NB, topk] kept key-block ids of query block b, ascending;
  *                            entries past blk_cnt are -1
  *   blk_cnt [rows, NB]       min(topk, b + 1)
+ *   order   [rows, NB]       the order in which minf_bs_attn takes the query
+ *                            blocks of a head: a permutation of 0 .. NB-1, or
+ *                            NULL for 0, 1, 2, ...  It has no influence on the
+ *                            result.  minf_build_bs_index sorts the query
+ *                            blocks by their first kept key block (then by
+ *                            block id): query blocks that attend the same key
+ *                            blocks (Section 2.2: the blocks cluster) then run
+ *                            at the same time on the same part of the chip and
+ *                            find each other's K/V tiles in its cache.  A caller
+ *                            that fills the index itself may leave it NULL.
  */
 typedef struct {
   int32_t *blk_idx;
   int32_t *blk_cnt;
+  int32_t *order;
   int32_t topk, block;
 } minf_bs_index;
 

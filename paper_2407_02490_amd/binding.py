@@ -48,7 +48,7 @@ class _VSIndex(ctypes.Structure):
 
 
 class _BSIndex(ctypes.Structure):
-    _fields_ = [("blk_idx", ctypes.c_void_p), ("blk_cnt", ctypes.c_void_p),
+    _fields_ = [("blk_idx", ctypes.c_void_p), ("blk_cnt", ctypes.c_void_p), ("order", ctypes.c_void_p),
                 ("topk", ctypes.c_int32), ("block", ctypes.c_int32)]
 
 
@@ -154,14 +154,16 @@ class VSIndex:
 class BSIndex:
     """Device buffers of a Block-Sparse index for `rows` heads (see minf_bs_index)."""
 
-    def __init__(self, rows, n_blocks, topk, device):
+    def __init__(self, rows, n_blocks, topk, device, with_order=True):
         self.rows, self.n_blocks, self.topk = rows, n_blocks, topk
         self.blk_idx = torch.empty(rows, n_blocks, topk, dtype=torch.int32, device=device)
         self.blk_cnt = torch.empty(rows, n_blocks, dtype=torch.int32, device=device)
+        self.order = torch.empty(rows, n_blocks, dtype=torch.int32, device=device) if with_order else None
 
     def c_struct(self):
         s = _BSIndex()
         s.blk_idx, s.blk_cnt = self.blk_idx.data_ptr(), self.blk_cnt.data_ptr()
+        s.order = self.order.data_ptr() if self.order is not None else None
         s.topk, s.block = self.topk, BLOCK
         return s
 
@@ -212,14 +214,17 @@ def vs_index_from_host(v_lists, s_lists, seq_len, device="cuda"):
     return idx
 
 
-def bs_index_from_host(blk_idx, blk_cnt, device="cuda"):
-    """Index buffers from host arrays blk_idx [rows, NB, topk], blk_cnt [rows, NB]."""
+def bs_index_from_host(blk_idx, blk_cnt, order=None, device="cuda"):
+    """Index buffers from host arrays blk_idx [rows, NB, topk], blk_cnt [rows, NB] and,
+    optionally, a processing order [rows, NB] (None: natural order)."""
     blk_idx = np.asarray(blk_idx, dtype=np.int32)
     blk_cnt = np.asarray(blk_cnt, dtype=np.int32)
     rows, NB, topk = blk_idx.shape
-    idx = BSIndex(rows, NB, topk, device)
+    idx = BSIndex(rows, NB, topk, device, with_order=order is not None)
     idx.blk_idx.copy_(torch.from_numpy(blk_idx))
     idx.blk_cnt.copy_(torch.from_numpy(blk_cnt))
+    if order is not None:
+        idx.order.copy_(torch.from_numpy(np.asarray(order, dtype=np.int32)))
     return idx
 
 

@@ -1585,11 +1585,17 @@ struct BsGen {
 
 template <bool ROWS256>
 __global__ __launch_bounds__(64) void bs_kernel(QKV x, HeadList hl, const int32_t *blk_idx,
-                                                const int32_t *blk_cnt, int topk, Sched sched) {
+                                                const int32_t *blk_cnt, const int32_t *order, int topk,
+                                                Sched sched) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   const int NB = x.N / BQ;
   int slot, b;
   if (!decode_wg(sched, slot, b)) return;
+  if (order) {
+    // position in the processing order -> query block (a permutation: every block is taken once)
+    b = __builtin_amdgcn_readfirstlane(order[(int64_t)slot * NB + b]);
+    if (b < 0 || b >= NB) return;
+  }
   const int head = __builtin_amdgcn_readfirstlane(hl.h[slot]);
   const int kvh = to_sgpr(head / x.group);
   const bf16_t *qh = x.q + head * x.q_sh;
@@ -1909,7 +1915,7 @@ hipError_t launch_ashape(const QKV &x, const HeadList &hl, int n_init, int n_loc
 }
 
 hipError_t launch_bs(const QKV &x, const HeadList &hl, const int32_t *blk_idx, const int32_t *blk_cnt,
-                     int topk, hipStream_t st) {
+                     const int32_t *order, int topk, hipStream_t st) {
   const int NB = x.N / BQ;
   const Sched s = make_sched(hl, x.group, NB);
   const size_t lds = 5 * HALF_BYTES;
@@ -1919,9 +1925,9 @@ hipError_t launch_bs(const QKV &x, const HeadList &hl, const int32_t *blk_idx, c
   hipError_t e = set_lds(fn, lds);
   if (e != hipSuccess) return e;
   if (rows256)
-    hipLaunchKernelGGL(bs_kernel<true>, dim3(s.per_xcd * 8), dim3(64), lds, st, x, hl, blk_idx, blk_cnt, topk, s);
+    hipLaunchKernelGGL(bs_kernel<true>, dim3(s.per_xcd * 8), dim3(64), lds, st, x, hl, blk_idx, blk_cnt, order, topk, s);
   else
-    hipLaunchKernelGGL(bs_kernel<false>, dim3(s.per_xcd * 8), dim3(64), lds, st, x, hl, blk_idx, blk_cnt, topk, s);
+    hipLaunchKernelGGL(bs_kernel<false>, dim3(s.per_xcd * 8), dim3(64), lds, st, x, hl, blk_idx, blk_cnt, order, topk, s);
   return hipGetLastError();
 }
 

@@ -872,6 +872,41 @@ __global__ __launch_bounds__(256) void bs_select_kernel(int NB, int slot0, int t
   ordered_select<256, false>(row, n, thr, take_eq, out, sh + 8);
 }
 
+// Processing order of the query blocks of one head: sorted by (first kept key block, block id).
+// One workgroup per head: the composite keys (first << 16 | block) of up to 16384 blocks are
+// sorted in LDS by a bitonic network (padded to a power of two with keys above every real one).
+constexpr int BS_ORDER_MAX = 16384;
+__global__ __launch_bounds__(1024) void bs_order_kernel(int NB, int topk, const int32_t *blk_idx, int32_t *order) {
+  __shared__ unsigned key[BS_ORDER_MAX];
+  const int slot = blockIdx.x, tid = threadIdx.x;
+  const int32_t *idx = blk_idx + (int64_t)slot * NB * topk;
+  int32_t *out = order + (int64_t)slot * NB;
+  int P = 1024;
+  while (P < NB) P <<= 1;
+  for (int b = tid; b < P; b += 1024) {
+    unsigned kf = 0xffffu;
+    if (b < NB) {
+      const int f = idx[(int64_t)b * topk];
+      kf = f < 0 ? 0u : (f > 0xfffe ? 0xfffeu : (unsigned)f);
+    }
+    key[b] = (kf << 16) | (unsigned)(b & 0xffff);
+  }
+  __syncthreads();
+  for (int k = 2; k <= P; k <<= 1)
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      for (int i = tid; i < P; i += 1024) {
+        const int l = i ^ j;
+        if (l > i) {
+          const unsigned a = key[i], c = key[l];
+          const bool up = (i & k) == 0;
+          if ((a > c) == up) { key[i] = c; key[l] = a; }
+        }
+      }
+      __syncthreads();
+    }
+  for (int b = tid; b < NB; b += 1024) out[b] = (int32_t)(key[b] & 0xffffu);
+}
+
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
@@ -929,8 +964,13 @@ size_t bs_index_ws_bytes(int N, int n_heads) {
   return b;
 }
 
+static __global__ void iota_kernel(int n, int period, int32_t *out) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) out[i] = i % period;
+}
+
 hipError_t launch_build_bs(const QKV &x, const HeadList &hl, int topk, int32_t *blk_idx,
-                           int32_t *blk_cnt, void *ws, hipStream_t st) {
+                           int32_t *blk_cnt, int32_t *order, void *ws, hipStream_t st) {
   const int NB = x.N / 64;
   KvMap km;
   km.n_kv = 0;
@@ -956,6 +996,12 @@ hipError_t launch_build_bs(const QKV &x, const HeadList &hl, int topk, int32_t *
                        (const float *)qpool, (const float *)kpool, scores, x.scale);
     hipLaunchKernelGGL(bs_select_kernel, dim3(NB, hb), dim3(256), 0, st, NB, s0, topk,
                        (const float *)scores, blk_idx, blk_cnt);
+  }
+  if (order) {
+    if (NB <= BS_ORDER_MAX)
+      hipLaunchKernelGGL(bs_order_kernel, dim3(hl.n), dim3(1024), 0, st, NB, topk, (const int32_t *)blk_idx, order);
+    else      // longer than the sort holds: natural order
+      hipLaunchKernelGGL(iota_kernel, dim3((hl.n * NB + 255) / 256), dim3(256), 0, st, hl.n * NB, NB, order);
   }
   return hipGetLastError();
 }

@@ -144,7 +144,7 @@ minf_status minf_build_bs_index(const minf_qkv *x, const int32_t *heads, int32_t
   for (int b = 0; b < x->batch; ++b) {
     const int64_t r = (int64_t)b * n_heads;
     hipError_t e = launch_build_bs(view(x, b), hl, topk, out->blk_idx + r * NB * topk,
-                                   out->blk_cnt + r * NB, ws, st);
+                                   out->blk_cnt + r * NB, out->order ? out->order + r * NB : nullptr, ws, st);
     if (e != hipSuccess) return MINF_ERR_HIP;
   }
   return MINF_OK;
@@ -208,7 +208,7 @@ minf_status minf_bs_attn(const minf_qkv *x, const int32_t *heads, int32_t n_head
   for (int b = 0; b < x->batch; ++b) {
     const int64_t r = (int64_t)b * n_heads;
     hipError_t e = launch_bs(view(x, b), hl, idx->blk_idx + r * NB * idx->topk, idx->blk_cnt + r * NB,
-                             idx->topk, st);
+                             idx->order ? idx->order + r * NB : nullptr, idx->topk, st);
     if (e != hipSuccess) return MINF_ERR_HIP;
   }
   return MINF_OK;

@@ -97,7 +97,7 @@ __device__ inline bool decode_wg(const Sched &s, int &slot, int &blk) {
 // attention launches (attn_kernels.hip)
 hipError_t launch_ashape(const QKV &x, const HeadList &hl, int n_init, int n_local, hipStream_t st);
 hipError_t launch_bs(const QKV &x, const HeadList &hl, const int32_t *blk_idx, const int32_t *blk_cnt,
-                     int topk, hipStream_t st);
+                     const int32_t *order, int topk, hipStream_t st);
 hipError_t launch_vs(const QKV &x, const HeadList &hl, const int32_t *v_idx, const int32_t *cover,
                      const uint32_t *cover_bits, const int32_t *counts, int nv, int ns,
                      int cover_words, hipStream_t st);
@@ -109,7 +109,7 @@ hipError_t launch_build_vs(const QKV &x, const HeadList &hl, int last_q, int nv,
                            int32_t *v_idx, int32_t *s_idx, int32_t *cover, uint32_t *cover_bits,
                            int32_t *counts, int cover_words, void *ws, hipStream_t st);
 hipError_t launch_build_bs(const QKV &x, const HeadList &hl, int topk, int32_t *blk_idx,
-                           int32_t *blk_cnt, void *ws, hipStream_t st);
+                           int32_t *blk_cnt, int32_t *order, void *ws, hipStream_t st);
 
 }  // namespace minf
 #endif

@@ -126,6 +126,23 @@ def test_bs_list_longer_than_one_lane_chunk(B, rng):
     assert_close_rows(o[0], want, "bs topk=100")
 
 
+def test_bs_processing_order_does_not_change_the_result(B, rng):
+    """The index may carry an order in which the query blocks are taken (any permutation):
+    the output is bit-identical to the natural order's."""
+    N, topk = 1344, 4                   # 21 blocks
+    NB = N // 64
+    q, k, v = random_qkv(6, 2, 1, N)
+    idxs = [random_bs_index(rng, NB, topk) for _ in range(2)]
+    bi, bc = np.stack([i for i, _ in idxs]), np.stack([c for _, c in idxs])
+    o_nat = run_heads(B.minf_bs_attn, q, k, v, [0, 1], B.bs_index_from_host(bi, bc))
+    order = np.stack([rng.permutation(NB), np.arange(NB)[::-1]])
+    o_perm = run_heads(B.minf_bs_attn, q, k, v, [0, 1], B.bs_index_from_host(bi, bc, order=order))
+    assert torch.equal(o_nat, o_perm)
+    for h in (0, 1):
+        want = O.bs_attention(to_f64(q[h]), to_f64(k[0]), to_f64(v[0]), idxs[h][0], idxs[h][1])
+        assert_close_rows(o_perm[h], want, f"bs with order, head {h}")
+
+
 def test_bs_full_index_is_dense(B):
     N = 512
     NB = N // 64

@@ -114,6 +114,10 @@ def check_bs_index(idx, r, Qh, Kh, topk):
     for b in range(NB):
         assert np.all(got[b, cnt[b]:] == -1)
         swaps += check_topk(got[b, :cnt[b]], s[b, :b + 1], topk, relative=False)
+    # processing order: the query blocks sorted by (first kept key block, block id) -- integer work, exact
+    order = idx.order[r].cpu().numpy()
+    want = np.lexsort((np.arange(NB), got[:, 0]))
+    assert np.array_equal(order, want)
     return got, cnt, swaps
 
 
