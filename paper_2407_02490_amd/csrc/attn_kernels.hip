@@ -1333,7 +1333,6 @@ struct WavePipe3 {
   int lane;
   Step d0, d1, d2;          // steps t (softmax), t+1 (logits), t+2 (K fetch)
   bool h0, h1, h2, hp;      // ... exist; hp: step t-1 exists (its P awaits the output update)
-  unsigned v0, v1, v2;      // LDS byte offsets of the V slots of steps t-1, t, t+1
 
   __device__ inline const char *row0(const char *head, unsigned rb, const Step &d) const {
     const unsigned kb = (unsigned)__builtin_amdgcn_readfirstlane(d.kbase);
@@ -1371,12 +1370,19 @@ struct WavePipe3 {
     dma_pair<ROWS256, 4>(a, rb, vo, dst); dma_pair<ROWS256, 6>(a, rb, vo, dst);
   }
 
-  __device__ inline void iter(int t, f32x16 (&s_cur)[1][2], f32x16 (&s_nxt)[1][2], bf16x8 (&p_prev)[2][2],
+  // Iteration t with PH = t mod 6: K of step s lives in K slot s mod 2, V of step s in V slot
+  // (s + 1) mod 3, so with the phase a template parameter every LDS address of the iteration is a
+  // lane constant plus an immediate (the loop is unrolled six times; with the V slot in a register
+  // every V operand read cost an address add on the vector ALU).
+  static constexpr unsigned v_slot(int i) { return (unsigned)(2 + i) * HALF_BYTES; }
+  template <int PH, bool FIRST>
+  __device__ inline void iter(f32x16 (&s_cur)[1][2], f32x16 (&s_nxt)[1][2], bf16x8 (&p_prev)[2][2],
                               bf16x8 (&p_cur)[2][2]) {
     MINF_WAIT_VMCNT(8);      // K of step t+1 (and everything older) has landed; V of step t may be in flight
-    const char *tK = buf.k((t + 1) & 1);
-    const char *tV = buf.lds + (t == 0 ? v1 : v0);        // no step -1: zero P times the rows of V(0)
-    const unsigned k_dst = lds_addr_of(buf.k(t & 1)), v_dst = lds_addr_of(buf.lds) + v2;
+    const char *tK = buf.k((PH + 1) & 1);
+    // V(t-1); in the very first iteration there is no step -1: zero P times the rows of V(0)
+    const char *tV = buf.lds + v_slot(FIRST ? 1 : PH % 3);
+    const unsigned k_dst = lds_addr_of(buf.k(PH & 1)), v_dst = lds_addr_of(buf.lds) + v_slot((PH + 2) % 3);
     const char *kt = row0(kh, k_rb, d2), *vt = row0(vh, v_rb, d1);
     bf16x8 kf[8], vf[8];
     kf[0] = lds_read_k(tK, lo.k[0]);
@@ -1476,7 +1482,6 @@ struct WavePipe3 {
     }
     // after the generator advanced in round 3: d0 = the step whose logits are now in s_nxt
     if (h0) fresh(s_nxt, d0);
-    const unsigned vr = v0; v0 = v1; v1 = v2; v2 = vr;
   }
   __device__ inline void run() {
     h0 = gen.next(d0);
@@ -1486,11 +1491,10 @@ struct WavePipe3 {
     d2 = d1;
     h2 = h1 && gen.next(d2);
     hp = false;
-    v0 = 2 * HALF_BYTES; v1 = 3 * HALF_BYTES; v2 = 4 * HALF_BYTES;
-    // K of steps 0, 1 into K slots 0, 1; V of step 0 into the slot of "step t" of iteration 0
+    // K of steps 0, 1 into K slots 0, 1; V of step 0 into V slot 1
     fetch_whole<true>(d0, lds_addr_of(buf.k(0)));
     fetch_whole<true>(d1, lds_addr_of(buf.k(1)));
-    fetch_whole<false>(d0, lds_addr_of(buf.lds) + v1);
+    fetch_whole<false>(d0, lds_addr_of(buf.lds) + v_slot(1));
     MINF_WAIT_VMCNT(0);
     f32x16 sa[1][2], sb[1][2];
     bf16x8 pa[2][2], pb[2][2];
@@ -1502,12 +1506,19 @@ struct WavePipe3 {
     fresh(sa, d0);
     // iteration t: d0 = step t (logits in hand), d1 = step t+1 (K landed), d2 = step t+2;
     // one iteration past the last step finishes its output update
-    int t = 0;
+    iter<0, true>(sa, sb, pa, pb);
     while (h0 || hp) {
-      iter(t, sa, sb, pa, pb);
+      iter<1, false>(sb, sa, pb, pa);
       if (!(h0 || hp)) break;
-      iter(t + 1, sb, sa, pb, pa);
-      t += 2;
+      iter<2, false>(sa, sb, pa, pb);
+      if (!(h0 || hp)) break;
+      iter<3, false>(sb, sa, pb, pa);
+      if (!(h0 || hp)) break;
+      iter<4, false>(sa, sb, pa, pb);
+      if (!(h0 || hp)) break;
+      iter<5, false>(sb, sa, pb, pa);
+      if (!(h0 || hp)) break;
+      iter<0, false>(sa, sb, pa, pb);
     }
     MINF_WAIT_VMCNT(0);      // the repeated loads of the last iterations
   }
