@@ -272,13 +272,15 @@ def tiles_dense(N, B=64):
     return np.arange(1, N // B + 1, dtype=np.int64)
 
 
-def tiles_ashape(N, n_init, n_local, B=64):
-    """Number of B-aligned key tiles that hold at least one permitted key."""
+def tiles_ashape(N, n_init, n_local, B=64, blocks=None):
+    """Number of B-aligned key tiles that hold at least one permitted key, per query block
+    (all of them, or only the listed ones: a long sequence has too many to mask one by one)."""
     NB = N // B
-    out = np.zeros(NB, dtype=np.int64)
-    for b in range(NB):
+    blocks = range(NB) if blocks is None else blocks
+    out = np.zeros(len(blocks), dtype=np.int64)
+    for n, b in enumerate(blocks):
         m = ashape_rows(b * B, (b + 1) * B, N, n_init, n_local).any(axis=0)
-        out[b] = m.reshape(NB, B).any(axis=1).sum()
+        out[n] = m.reshape(NB, B).any(axis=1).sum()
     return out
 
 
