@@ -146,6 +146,17 @@ class Layer:
             if not ms:
                 continue
             e = {"ms": round(float(np.mean(ms)), 4), "ms_min": round(float(np.min(ms)), 4)}
+            if k == "vs_index":
+                # one pass over K per K/V head in use, the estimating queries, the two line-score rows
+                kv = len({h // (self.Hq // self.x.n_kv_heads) for h in self.vs_heads})
+                by = kv * self.N * 256 + len(self.vs_heads) * (64 * 256 + 2 * self.N * 4)
+                e.update({"algorithmic_bytes": by, "gb_per_s": round(by / (e["ms"] * 1e-3) / 1e9, 1),
+                          "k_passes_run": "2 per query head (row max/sum, then normalised sums)"})
+            if k == "bs_index":
+                # all of Q of the heads and K of their K/V heads, once
+                kv = len({h // (self.Hq // self.x.n_kv_heads) for h in self.bs_heads})
+                by = (len(self.bs_heads) + kv) * self.N * 256
+                e.update({"algorithmic_bytes": by, "gb_per_s": round(by / (e["ms"] * 1e-3) / 1e9, 1)})
             if k in tiles:
                 e["tiles"] = tiles[k]
                 e["tflops"] = round(tiles[k] * FT / (e["ms"] * 1e-3) / 1e12, 2)
@@ -314,7 +325,7 @@ def read_traffic(kernel_tag):
             for line in open(os.path.join(pdir, fn)):
                 if line.strip().startswith(key):
                     try:
-                        return float(line.split(":", 1)[1].split()[0])
+                        return float(line.strip()[len(key):].split()[0])
                     except ValueError:
                         return None
     return None
