@@ -9,6 +9,7 @@ import pytest
 import torch
 
 from oracle import minference_oracle as O
+from paper_2407_02490_amd import workloads as W
 from tests.helpers import assert_close_rows, random_qkv, to_f64
 
 pytestmark = pytest.mark.gpu
@@ -236,6 +237,31 @@ def test_vs_many_columns_more_than_one_round(B, rng):
     o = run_heads(B.minf_vs_attn, q, k, v, [0], dev)
     want = O.vs_attention(to_f64(q[0]), to_f64(k[0]), to_f64(v[0]), Vl, Sl, Bm=64)
     assert_close_rows(o[0], want, "vs 1500 columns")
+
+
+def test_outputs_are_bit_reproducible(B, rng):
+    """No kernel of the path accumulates through atomics or in a timing-dependent order: two runs
+    on the same inputs give identical bits (all four attention calls, index from the GPU)."""
+    N = 4096
+    x = W.make_config("c4", device="cuda", N=N, n_q_heads=8, n_kv_heads=2)
+    heads = list(range(8))
+    outs = []
+    for _ in range(2):
+        vi = B.alloc_vs_index(8, 100, 300, N)
+        ws = torch.empty(B.minf_vs_index_workspace_bytes(x.q, x.k, 8, 64), dtype=torch.uint8, device="cuda")
+        B.minf_build_vs_index(x.q, x.k, heads, 64, 100, 300, vi, ws)
+        bi = B.alloc_bs_index(8, N, 9)
+        ws2 = torch.empty(B.minf_bs_index_workspace_bytes(x.q, x.k, 8), dtype=torch.uint8, device="cuda")
+        B.minf_build_bs_index(x.q, x.k, heads, 9, bi, ws2)
+        o = [torch.empty_like(x.q) for _ in range(4)]
+        B.minf_vs_attn(x.q, x.k, x.v, o[0], heads, vi)
+        B.minf_bs_attn(x.q, x.k, x.v, o[1], heads, bi)
+        B.minf_ashape_attn(x.q, x.k, x.v, o[2], heads, 128, 512)
+        B.minf_dense_attn(x.q, x.k, x.v, o[3], heads)
+        torch.cuda.synchronize()
+        outs.append(o + [vi.v_idx.clone(), vi.s_idx.clone(), vi.cover_bits.clone(), bi.blk_idx.clone(), bi.order.clone()])
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
 
 
 def test_bad_arguments_are_rejected_before_launch(B):
