@@ -145,3 +145,49 @@ def test_c4_mixed_1m(B):
     for b in sample_blocks(NB, [16, 64, 80], 4, 6):
         want = O.ashape_attention(Qh, Kh, Vh, c["n_init"], c["n_local"], 64 * b, 64 * b + 64)
         assert_close_rows(o[h, 64 * b:64 * b + 64], want, f"c4 A-shape head {h} block {b}")
+
+
+def test_ragged_medium_length_mixed(B):
+    """A length that is a multiple of 64 and of nothing larger (1025 blocks): the last
+    1024-key chunk of the score kernels holds one tile, rows of block logits are not 16-byte
+    aligned (general selection path), the last shared-tile workgroup has three idle waves."""
+    N = 64 * 1025
+    x = W.make_config("c4", device="cuda", N=N, n_q_heads=8, n_kv_heads=2)
+    heads_vs, heads_bs, heads_a = [0, 1, 5], [2, 6, 7], [3, 4]
+    nv, ns, topk = 300, 2000, 40
+    vsi = B.alloc_vs_index(len(heads_vs), nv, ns, N)
+    vws = torch.empty(B.minf_vs_index_workspace_bytes(x.q, x.k, len(heads_vs), 64), dtype=torch.uint8, device="cuda")
+    bsi = B.alloc_bs_index(len(heads_bs), N, topk)
+    bws = torch.empty(B.minf_bs_index_workspace_bytes(x.q, x.k, len(heads_bs)), dtype=torch.uint8, device="cuda")
+    o = torch.full_like(x.q, float("nan"))
+    B.minf_build_vs_index(x.q, x.k, heads_vs, 64, nv, ns, vsi, vws)
+    B.minf_build_bs_index(x.q, x.k, heads_bs, topk, bsi, bws)
+    B.minf_ashape_attn(x.q, x.k, x.v, o, heads_a, 1024, 4096)
+    B.minf_vs_attn(x.q, x.k, x.v, o, heads_vs, vsi)
+    B.minf_bs_attn(x.q, x.k, x.v, o, heads_bs, bsi)
+    torch.cuda.synchronize()
+    assert not torch.isnan(o.float()).any()
+    NB = N // 64
+    blocks = sample_blocks(NB, [15, 16, 17, 63, 64, 65, 80, 81, NB - 2], 4, 5)
+    r, h = 1, heads_vs[1]
+    Qh, Kh, Vh = x.head_f64(h)
+    Vo, So, col, diag = O.vs_index(Qh, Kh, 64, nv, ns)
+    Vg, Sg = vsi.v_idx[r].cpu().numpy(), vsi.s_idx[r].cpu().numpy()
+    check_topk(Vg, col, nv)
+    check_topk(Sg, diag, ns)
+    for b in blocks:
+        assert_close_rows(o[h, 64 * b:64 * b + 64], O.vs_attention(Qh, Kh, Vh, Vg, Sg, 64 * b, 64 * b + 64), f"ragged VS block {b}")
+    r, h = 2, heads_bs[2]
+    Qh, Kh, Vh = x.head_f64(h)
+    io, co, s = O.bs_index(Qh, Kh, 64, topk)
+    got, cnt = bsi.blk_idx[r].cpu().numpy(), bsi.blk_cnt[r].cpu().numpy()
+    assert np.array_equal(cnt, co)
+    for b in range(NB):
+        check_topk(got[b, :cnt[b]], s[b, :b + 1], topk, relative=False)
+    assert np.array_equal(bsi.order[r].cpu().numpy(), np.lexsort((np.arange(NB), got[:, 0])))
+    for b in blocks:
+        assert_close_rows(o[h, 64 * b:64 * b + 64], O.bs_attention(Qh, Kh, Vh, got, cnt, 64 * b, 64 * b + 64), f"ragged BS block {b}")
+    h = heads_a[0]
+    Qh, Kh, Vh = x.head_f64(h)
+    for b in blocks:
+        assert_close_rows(o[h, 64 * b:64 * b + 64], O.ashape_attention(Qh, Kh, Vh, 1024, 4096, 64 * b, 64 * b + 64), f"ragged A-shape block {b}")
