@@ -346,7 +346,7 @@ def main():
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (heads would shard across "
-              "GPUs without any exchange inside attention, see DESIGN.md)", file=sys.stderr)
+              "GPUs without any exchange inside attention)", file=sys.stderr)
         sys.exit(2)
     B.lib()
     torch.cuda.set_device(0)
