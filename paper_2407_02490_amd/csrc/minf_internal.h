@@ -72,9 +72,9 @@ inline Sched make_sched(const HeadList &hl, int group, int n_blk) {
   }
   return s;
 }
-// Returns false if this workgroup has no work item.
-__device__ inline bool decode_wg(const Sched &s, int &slot, int &blk) {
-  const int hw = blockIdx.x;
+// Work item of position hw (0 <= hw < 8 * per_xcd) of the launch order; false if that position
+// holds none.  Plain integer arithmetic: also compiled for the host, where a test enumerates it.
+__host__ __device__ inline bool decode_item(const Sched &s, int hw, int &slot, int &blk) {
   const int xcd = hw & 7;
   int seq = hw >> 3;
   // every head contributes ls * stripe items per XCD, so the chunk follows from the head position
@@ -92,6 +92,10 @@ __device__ inline bool decode_wg(const Sched &s, int &slot, int &blk) {
   slot = c0 + r % csize;
   blk = s.n_blk - 1 - rank;
   return rank < s.n_blk;
+}
+// Returns false if this workgroup has no work item.
+__device__ inline bool decode_wg(const Sched &s, int &slot, int &blk) {
+  return decode_item(s, blockIdx.x, slot, blk);
 }
 
 // attention launches (attn_kernels.hip)
