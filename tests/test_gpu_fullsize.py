@@ -191,3 +191,51 @@ def test_ragged_medium_length_mixed(B):
     Qh, Kh, Vh = x.head_f64(h)
     for b in blocks:
         assert_close_rows(o[h, 64 * b:64 * b + 64], O.ashape_attention(Qh, Kh, Vh, 1024, 4096, 64 * b, 64 * b + 64), f"ragged A-shape block {b}")
+
+
+def test_two_million_tokens_one_head(B):
+    """Beyond the benchmark sizes: 2M tokens (32768 blocks), one head per pattern on one K/V
+    head.  Rows of block logits are longer than the selection kernel holds in registers, the
+    processing order falls back to the natural one (more blocks than its sort holds), row
+    offsets pass 2^29 bytes."""
+    N = 1 << 21
+    x = W.make_config("c4", device="cuda", N=N, n_q_heads=3, n_kv_heads=1)
+    NB = N // 64
+    nv, ns, topk = 1000, 6096, 100
+    vsi = B.alloc_vs_index(1, nv, ns, N)
+    vws = torch.empty(B.minf_vs_index_workspace_bytes(x.q, x.k, 1, 64), dtype=torch.uint8, device="cuda")
+    bsi = B.alloc_bs_index(1, N, topk)
+    bws = torch.empty(B.minf_bs_index_workspace_bytes(x.q, x.k, 1), dtype=torch.uint8, device="cuda")
+    o = torch.full_like(x.q, float("nan"))
+    B.minf_build_vs_index(x.q, x.k, [0], 64, nv, ns, vsi, vws)
+    B.minf_build_bs_index(x.q, x.k, [1], topk, bsi, bws)
+    B.minf_vs_attn(x.q, x.k, x.v, o, [0], vsi)
+    B.minf_bs_attn(x.q, x.k, x.v, o, [1], bsi)
+    B.minf_ashape_attn(x.q, x.k, x.v, o, [2], 1024, 4096)
+    torch.cuda.synchronize()
+    del vws, bws
+    torch.cuda.empty_cache()
+    assert not torch.isnan(o[:, -1].float()).any()
+    tau = 1.0 / np.sqrt(128.0)
+    blocks = sample_blocks(NB, [16383, 16384, 16385], 2, 8)
+    Qh, Kh, Vh = x.head_f64(0)
+    Vo, So, col, diag = O.vs_index(Qh, Kh, 64, nv, ns)
+    Vg, Sg = vsi.v_idx[0].cpu().numpy(), vsi.s_idx[0].cpu().numpy()
+    print("2M VS tolerated index swaps:", check_topk(Vg, col, nv) + check_topk(Sg, diag, ns))
+    for b in blocks:
+        want = O.vs_attention(Qh, Kh, Vh, Vg, Sg, 64 * b, 64 * b + 64)
+        assert_close_rows(o[0, 64 * b:64 * b + 64], want, f"2M VS block {b}")
+    Qh, Kh, Vh = x.head_f64(1)
+    Qp, Kp = O.bs_pool(Qh), O.bs_pool(Kh)
+    got, cnt = bsi.blk_idx[0].cpu().numpy(), bsi.blk_cnt[0].cpu().numpy()
+    assert np.array_equal(cnt, np.minimum(topk, np.arange(1, NB + 1)))
+    assert np.array_equal(bsi.order[0].cpu().numpy(), np.arange(NB))
+    for b in blocks + [99, 100, 16500, 30000]:
+        bs_row_check(got[b], cnt[b], Qp, Kp, b, topk, tau)
+    for b in blocks:
+        want = O.bs_attention(Qh, Kh, Vh, got, cnt, 64 * b, 64 * b + 64)
+        assert_close_rows(o[1, 64 * b:64 * b + 64], want, f"2M BS block {b}")
+    Qh, Kh, Vh = x.head_f64(2)
+    for b in blocks:
+        want = O.ashape_attention(Qh, Kh, Vh, 1024, 4096, 64 * b, 64 * b + 64)
+        assert_close_rows(o[2, 64 * b:64 * b + 64], want, f"2M A-shape block {b}")
