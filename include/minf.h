@@ -101,8 +101,10 @@ typedef struct {
  *                            block id): query blocks that attend the same key
  *                            blocks (Section 2.2: the blocks cluster) then run
  *                            at the same time on the same part of the chip and
- *                            find each other's K/V tiles in its cache.  A caller
- *                            that fills the index itself may leave it NULL.
+ *                            find each other's K/V tiles in its cache (up to
+ *                            32768 blocks = 2M tokens; longer sequences get the
+ *                            natural order).  A caller that fills the index
+ *                            itself may leave it NULL.
  */
 typedef struct {
   int32_t *blk_idx;

@@ -873,11 +873,12 @@ __global__ __launch_bounds__(256) void bs_select_kernel(int NB, int slot0, int t
 }
 
 // Processing order of the query blocks of one head: sorted by (first kept key block, block id).
-// One workgroup per head: the composite keys (first << 16 | block) of up to 16384 blocks are
-// sorted in LDS by a bitonic network (padded to a power of two with keys above every real one).
-constexpr int BS_ORDER_MAX = 16384;
+// One workgroup per head: the composite keys (first << 16 | block) of up to 32768 blocks are
+// sorted in LDS (4 bytes per block, up to 128 KiB) by a bitonic network (padded to a power of
+// two with keys above every real one).
+constexpr int BS_ORDER_MAX = 32768;
 __global__ __launch_bounds__(1024) void bs_order_kernel(int NB, int topk, const int32_t *blk_idx, int32_t *order) {
-  __shared__ unsigned key[BS_ORDER_MAX];
+  extern __shared__ unsigned key[];
   const int slot = blockIdx.x, tid = threadIdx.x;
   const int32_t *idx = blk_idx + (int64_t)slot * NB * topk;
   int32_t *out = order + (int64_t)slot * NB;
@@ -998,8 +999,15 @@ hipError_t launch_build_bs(const QKV &x, const HeadList &hl, int topk, int32_t *
                        (const float *)scores, blk_idx, blk_cnt);
   }
   if (order) {
-    if (NB <= BS_ORDER_MAX)
-      hipLaunchKernelGGL(bs_order_kernel, dim3(hl.n), dim3(1024), 0, st, NB, topk, (const int32_t *)blk_idx, order);
+    if (NB <= BS_ORDER_MAX) {
+      int P = 1024;
+      while (P < NB) P <<= 1;
+      const size_t lds = (size_t)P * sizeof(unsigned);
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs_order_kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL(bs_order_kernel, dim3(hl.n), dim3(1024), lds, st, NB, topk, (const int32_t *)blk_idx, order);
+    }
     else      // longer than the sort holds: natural order
       hipLaunchKernelGGL(iota_kernel, dim3((hl.n * NB + 255) / 256), dim3(256), 0, st, hl.n * NB, NB, order);
   }
