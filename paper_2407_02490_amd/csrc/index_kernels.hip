@@ -422,6 +422,26 @@ __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int la
         }
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
+        float &m_run = nb == 0 ? m_run0 : m_run1;
+        float &l_run = nb == 0 ? l_run0 : l_run1;
+        if (!diag_tile && r_min == 0) {
+          // no element of the tile is masked (all but the last tile of a head): the maximum is
+          // taken over the raw logits and the scale rides in the exponent's multiply-add
+          float mx = s[0][nb][0];
+#pragma unroll
+          for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) mx = fmaxf(mx, s[mb][nb][e]);
+          const float m_new = fmaxf(m_run, mx * x.c_log2);
+          float sum = 0.f;
+#pragma unroll
+          for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) sum += fast_exp2(fmaf(s[mb][nb][e], x.c_log2, -m_new));
+          l_run = l_run * fast_exp2(m_run - m_new) + sum;
+          m_run = m_new;
+          continue;
+        }
         const int r = 32 * nb + n, p = N - 64 + r;
         float mx = -INFINITY;
 #pragma unroll
@@ -437,8 +457,6 @@ __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int la
             s[mb][nb][e] = v;
             mx = fmaxf(mx, v);
           }
-        float &m_run = nb == 0 ? m_run0 : m_run1;
-        float &l_run = nb == 0 ? l_run0 : l_run1;
         const float m_new = fmaxf(m_run, mx);
         const float m_use = m_new == -INFINITY ? 0.f : m_new;
         float sum = 0.f;
