@@ -137,8 +137,20 @@ class Layer:
             out["bs_attn"] = int(C.bs_index_tiles(self.bs_idx).sum())
         return out
 
+    def nnz(self):
+        """Permitted (query, key) pairs per attention call: the useful work, 4 * d FLOP each."""
+        out = {}
+        if self.a_heads:
+            out["ashape_attn"] = int(C.nnz_ashape(self.N, self.cfg["n_init"], self.cfg["n_local"]).sum()) * len(self.a_heads)
+        if self.vs_heads:
+            out["vs_attn"] = int(C.vs_index_nnz(self.vs_idx, self.N).sum())
+        if self.bs_heads:
+            out["bs_attn"] = int(C.bs_index_nnz(self.bs_idx).sum())
+        return out
+
     def report(self, wall_ms):
         tiles = self.tiles()
+        nnz = self.nnz()
         r = {"workload": self.name, "seq_len": self.N, "ms_per_layer": round(wall_ms, 4), "calls": {}}
         tot_tiles = 0
         for k, t in self.t.items():
@@ -161,6 +173,9 @@ class Layer:
                 e["tiles"] = tiles[k]
                 e["tflops"] = round(tiles[k] * FT / (e["ms"] * 1e-3) / 1e12, 2)
                 e["frac_of_bf16_peak"] = round(e["tflops"] / PEAK_BF16_TFLOPS, 4)
+                # FLOPs of the permitted pairs only (a tile also pays for its masked part)
+                e["useful_tflops"] = round(4 * 128 * nnz[k] / (e["ms"] * 1e-3) / 1e12, 2)
+                e["mask_fill_of_tiles"] = round(nnz[k] / (tiles[k] * 64 * 64), 4)
                 tot_tiles += tiles[k]
             r["calls"][k] = e
         r["tiles"] = tot_tiles

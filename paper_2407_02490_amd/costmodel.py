@@ -70,6 +70,79 @@ def tiles_vs(N, v_idx, runs):
     return out
 
 
+# ---------------------------------------------------------------------------
+# Permitted (query, key) pairs per query block: the "useful" work, 4 * d FLOP per
+# pair, as opposed to the tile count above, which also pays for the masked part
+# of every tile a kernel has to touch.
+# ---------------------------------------------------------------------------
+def nnz_dense(N):
+    q0 = BLOCK * np.arange(N // BLOCK, dtype=np.int64)
+    return BLOCK * q0 + BLOCK * (BLOCK + 1) // 2
+
+
+def nnz_ashape(N, n_init, n_local):
+    i = np.arange(N, dtype=np.int64)
+    n_init, n_local = min(n_init, N), min(n_local, N)
+    sink = np.minimum(i + 1, n_init)
+    win_lo = np.maximum(np.maximum(i - n_local + 1, n_init), 0)
+    win = np.maximum(i - win_lo + 1, 0)
+    return (sink + win).reshape(-1, BLOCK).sum(axis=1)
+
+
+def nnz_bs(blk_idx, blk_cnt):
+    """blk_idx [NB, topk], blk_cnt [NB]: whole blocks below the diagonal, the lower triangle on it."""
+    blk_idx = np.asarray(blk_idx, dtype=np.int64)
+    cnt = np.asarray(blk_cnt, dtype=np.int64)
+    NB, topk = blk_idx.shape
+    valid = (np.arange(topk)[None, :] < cnt[:, None]) & (blk_idx >= 0)
+    b = np.arange(NB, dtype=np.int64)[:, None]
+    below = (valid & (blk_idx < b)).sum(axis=1)
+    diag = (valid & (blk_idx == b)).any(axis=1)
+    return BLOCK * BLOCK * below + diag * (BLOCK * (BLOCK + 1) // 2)
+
+
+def nnz_vs(N, v_idx, runs):
+    """Run [t0, t1) of block b (first row q0) permits key q0 - t for every t in the run with
+    0 <= q0 - t: all 64 rows if t >= 0, the rows at or below the key (64 + t of them) if t < 0.
+    A kept vertical outside every run counts for the rows at or below it."""
+    NB = N // BLOCK
+    q0 = BLOCK * np.arange(NB, dtype=np.int64)[:, None]
+    runs = np.asarray(runs, dtype=np.int64).reshape(-1, 2)
+    v = np.asarray(v_idx, dtype=np.int64)
+    out = np.zeros(NB, dtype=np.int64)
+    if runs.size:
+        t0, t1 = runs[None, :, 0], runs[None, :, 1]
+        full = np.maximum(np.minimum(t1, q0 + 1) - np.maximum(t0, 0), 0)           # t >= 0, key >= 0
+        a, e = np.maximum(t0, -(BLOCK - 1)), np.minimum(t1, 0)                      # t in [a, e), t < 0
+        m = np.maximum(e - a, 0)
+        # sum over t = a .. e-1 of (64 + t); keys q0 - t <= q0 + 63 < N always hold for whole blocks
+        part = m * BLOCK + (a + e - 1) * m // 2
+        out += (BLOCK * full + part).sum(axis=1)
+    if v.size:
+        for lo in range(0, NB, 1024):
+            hi = min(NB, lo + 1024)
+            t = q0[lo:hi] - v[None, :]
+            rows = np.clip(BLOCK + np.minimum(t, 0), 0, BLOCK)                     # 64 if v <= q0, fewer above
+            if runs.size:
+                j = np.searchsorted(runs[:, 0], t, side="right") - 1
+                inside = (j >= 0) & (t < runs[np.maximum(j, 0), 1])
+                rows = np.where(inside, 0, rows)
+            out[lo:hi] += rows.sum(axis=1)
+    return out
+
+
+def vs_index_nnz(idx, N):
+    counts = idx.counts.cpu().numpy()
+    v_idx = idx.v_idx.cpu().numpy()
+    cover = idx.cover.cpu().numpy()
+    return np.stack([nnz_vs(N, v_idx[r, :counts[r, 0]], cover[r, :counts[r, 2]]) for r in range(idx.rows)])
+
+
+def bs_index_nnz(idx):
+    bi, bc = idx.blk_idx.cpu().numpy(), idx.blk_cnt.cpu().numpy()
+    return np.stack([nnz_bs(bi[r], bc[r]) for r in range(idx.rows)])
+
+
 def vs_index_tiles(idx, N):
     """Per-head tile counts [rows, NB] of a binding.VSIndex (copies it to the host)."""
     counts = idx.counts.cpu().numpy()

@@ -49,3 +49,26 @@ def test_bs_speedup_closed_form():
     cnt = np.minimum(kb, np.arange(1, NB + 1))
     ratio = C.tiles_dense(N).sum() / C.tiles_bs(cnt).sum()
     assert abs(ratio - N / (2 * 64 * kb)) / ratio < 0.03
+
+
+def block_sums(mask_rows):
+    return mask_rows.sum(axis=1).reshape(-1, 64).sum(axis=1)
+
+
+def test_permitted_pair_counts_match_the_oracle_masks(rng=np.random.default_rng(5)):
+    """The useful-work counters against explicit masks of the oracle on a short sequence."""
+    N = 1024
+    NB = N // 64
+    assert np.array_equal(C.nnz_dense(N), block_sums(O.causal_rows(0, N, N)))
+    for n_init, n_local in [(64, 128), (100, 200), (0, 65), (5, 1), (2000, 3)]:
+        assert np.array_equal(C.nnz_ashape(N, n_init, n_local), block_sums(O.ashape_rows(0, N, N, n_init, n_local)))
+    idx = -np.ones((NB, 5), np.int64)
+    cnt = np.zeros(NB, np.int64)
+    for b in range(NB):
+        c = min(5, b + 1)
+        idx[b, :c], cnt[b] = np.sort(rng.choice(b + 1, c, replace=False)), c
+    assert np.array_equal(C.nnz_bs(idx, cnt), block_sums(O.bs_rows(0, N, N, idx, cnt)))
+    for V, S in [([3, 70, 71, 300, 1023], [0, 5, 64, 200, 201, 450]), ([], [0]), ([5], list(range(N))),
+                 (list(range(0, N, 37)), [0, 1, 2, 3, 130, 131, 400, 1000]), ([600, 601], [500])]:
+        want = block_sums(O.vs_rows(0, N, N, np.asarray(V, dtype=np.int64), np.asarray(S, dtype=np.int64), 64))
+        assert np.array_equal(C.nnz_vs(N, V, runs_of(np.asarray(S, dtype=np.int64), N)), want), (V[:3], S[:3])
