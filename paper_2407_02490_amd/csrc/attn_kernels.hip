@@ -1063,17 +1063,17 @@ __device__ inline void dma_pair(const char *step_row0, unsigned rb, const unsign
 }
 // Gathered rows: lane L of block blk fetches chunk c of row cols[4 blk + L / 16];
 // the byte offset key * rb + 16 c fits 32 bits (checked on the host: N rb < 2^32),
-// key < 2^24.  KEY_NONE entries read row 0 (the caller masks them).
+// key < 2^24.  KEY_NONE entries read the last row (the caller masks them): one unsigned minimum
+// with N - 1 instead of a compare and a select.
 template <int B>
 __device__ inline void dma_pair_gather(const char *head, unsigned rb, const int *cols, unsigned lds_step,
-                                       int lane) {
+                                       int lane, unsigned last_row) {
   const int rl = lane >> 4, cpos = lane & 15;
 #pragma unroll
   for (int j = 0; j < 2; ++j) {
     const int blk = B + j, r = 4 * blk + rl;
-    int key = cols[r];
-    key = key == KEY_NONE ? 0 : key;
-    const unsigned ofs = __umul24((unsigned)key, rb) + (unsigned)((cpos ^ swz_f(r)) << 4);
+    const unsigned key = min((unsigned)cols[r], last_row);
+    const unsigned ofs = __umul24(key, rb) + (unsigned)((cpos ^ swz_f(r)) << 4);
     dma16_su(head, ofs, lds_step + blk * 1024);
   }
 }
@@ -1123,8 +1123,8 @@ struct WavePipe {
     // before its round 2
     constexpr bool k_now = R < 4;
     if (GATHER) {
-      if (k_now) dma_pair_gather<2 * (R & 3)>(kh, k_rb, kcols, k_dst, lane);
-      else dma_pair_gather<2 * (R & 3)>(vh, v_rb, vcols, v_dst, lane);
+      if (k_now) dma_pair_gather<2 * (R & 3)>(kh, k_rb, kcols, k_dst, lane, (unsigned)N - 1u);
+      else dma_pair_gather<2 * (R & 3)>(vh, v_rb, vcols, v_dst, lane, (unsigned)N - 1u);
     } else {
       if (k_now) dma_pair<ROWS256, 2 * (R & 3)>(kt, k_rb, dk.voff, k_dst);
       else dma_pair<ROWS256, 2 * (R & 3)>(vt, v_rb, dv.voff, v_dst);
@@ -1267,8 +1267,9 @@ struct WavePipe {
     const char *head = IS_K ? kh : vh;
     const unsigned rb = IS_K ? k_rb : v_rb;
     if (GATHER) {
-      dma_pair_gather<0>(head, rb, d.cols, dst, lane); dma_pair_gather<2>(head, rb, d.cols, dst, lane);
-      dma_pair_gather<4>(head, rb, d.cols, dst, lane); dma_pair_gather<6>(head, rb, d.cols, dst, lane);
+      const unsigned last = (unsigned)N - 1u;
+      dma_pair_gather<0>(head, rb, d.cols, dst, lane, last); dma_pair_gather<2>(head, rb, d.cols, dst, lane, last);
+      dma_pair_gather<4>(head, rb, d.cols, dst, lane, last); dma_pair_gather<6>(head, rb, d.cols, dst, lane, last);
     } else {
       const char *a = row0(head, rb, d);
       const unsigned (&vo)[4] = IS_K ? dk.voff : dv.voff;
