@@ -697,27 +697,28 @@ struct AshapeLoop {
   float c_log2;
   int lane;
   int T, T1, s2;
-  char *lds;                 // K slots at lds + i * 16 KiB, V slots at lds + (3 + i) * 16 KiB
-  unsigned ra, rb, rc;       // ring: byte offsets of slots t mod 3, (t+1) mod 3, (t+2) mod 3
+  // K slots at lds + i * 16 KiB, V slots at lds + (4 + i) * 16 KiB, i < 4: tile s lives in slot
+  // s mod 4.  Three tiles of each kind are live at a time; the fourth slot makes the ring length a
+  // power of two, so that the loop, unrolled four times, has every slot as a compile-time constant
+  // (with the slot offset in a register every LDS operand read cost an address add: 51 of the
+  // about 1100 instructions of an iteration).
+  char *lds;
+  static constexpr unsigned k_slot(int i) { return (unsigned)(i & 3) * TILE_BYTES; }
+  static constexpr unsigned v_slot(int i) { return (unsigned)(4 + (i & 3)) * TILE_BYTES; }
   int kb1, kb2, kb3, ti3;    // key bases of tiles t+1, t+2, t+3 (indices clamped to T-1); index of the last
   int cls_cur;
   bool has_ref;
 
   // scalar operands of the coming iteration
-  const char *kt_, *vt_, *tK_, *tV_;
-  unsigned k_dst_, v_dst_;
+  const char *kt_, *vt_;
   int cls_nxt_;
 
   __device__ inline int tile_base(int i) const { return i < T1 ? i * BK : s2 + (i - T1) * BK; }
 
-  // for iteration t, from the ring and tile state of iteration t
+  // for iteration t, from the tile state of iteration t
   __device__ inline void prepare(int t) {
-    kt_ = d.kw + (size_t)kb3 * d.k_rb;                                  // K(t+3) -> slot t mod 3
-    vt_ = d.vw + (size_t)kb1 * d.v_rb;                                  // V(t+1) -> slot (t+1) mod 3
-    k_dst_ = lds_addr_of(lds) + ra + d.lds_w;
-    v_dst_ = lds_addr_of(lds) + 3 * TILE_BYTES + rb + d.lds_w;
-    tK_ = lds + rb;                                                     // K(t+1)
-    tV_ = lds + 3 * TILE_BYTES + (t == 0 ? ra : rc);                    // V(t-1); V(0) for the zero P(-1)
+    kt_ = d.kw + (size_t)kb3 * d.k_rb;                                  // K(t+3) -> slot (t+3) mod 4
+    vt_ = d.vw + (size_t)kb1 * d.v_rb;                                  // V(t+1) -> slot (t+1) mod 4
     cls_nxt_ = t + 1 < T ? cls.of(kb1) : 0;
   }
 
@@ -728,23 +729,28 @@ struct AshapeLoop {
   template <int I>
   __device__ inline void load_v(int kb, unsigned slot_ofs) const {
     dma_block<ROWS256, I>(d.vw + (size_t)kb * d.v_rb, d.v_rb, d.v_voff[I],
-                          lds_addr_of(lds) + 3 * TILE_BYTES + slot_ofs + d.lds_w);
+                          lds_addr_of(lds) + 4 * TILE_BYTES + slot_ofs + d.lds_w);
   }
   // first operands of an iteration (k-step 0 of both key blocks, output update steps 0, 1): read
   // during the last round of the iteration before
   struct Lead {
     bf16x8 k[2], v[2];
   };
+  // for the iteration of phase PH: K(t+1) and V(t-1) (V(0) in the very first one: zero P(-1))
+  template <int PH, bool FIRST>
   __device__ inline void read_lead(Lead &ld) const {
-    ld.k[0] = lds_read_k(tK_, lo.k[0]);
-    ld.k[1] = lds_read_k(tK_, lo.k[0] + HALF_BYTES);
-    ld.v[0] = lds_read_vt(tV_, lo.v[0][0], lo.v[0][1]);
-    ld.v[1] = lds_read_vt(tV_, lo.v[1][0], lo.v[1][1]);
+    const char *tK = lds + k_slot(PH + 1), *tV = lds + v_slot(FIRST ? 0 : PH + 3);
+    ld.k[0] = lds_read_k(tK, lo.k[0]);
+    ld.k[1] = lds_read_k(tK, lo.k[0] + HALF_BYTES);
+    ld.v[0] = lds_read_vt(tV, lo.v[0][0], lo.v[0][1]);
+    ld.v[1] = lds_read_vt(tV, lo.v[1][0], lo.v[1][1]);
   }
 
+  // Iteration t, PH = t mod 4.
+  template <int PH, bool FIRST>
   __device__ inline void iter(int t, f32x16 (&s_cur)[2][2], f32x16 (&s_nxt)[2][2], bf16x8 (&p_prev)[2][2][2],
                               bf16x8 (&p_cur)[2][2][2], Lead &lead) {
-    const char *tK = tK_, *tV = tV_;
+    const char *tK = lds + k_slot(PH + 1), *tV = lds + v_slot(FIRST ? 0 : PH + 3);
     auto fetch_v = [&](int i) {            // PV step i = (mb, t, db)
       const int mb = i / 8, tt = (i / 4) & 1, db = i & 3;
       const int base = (32 * mb + 16 * tt) * ROW_BYTES;
@@ -757,12 +763,12 @@ struct AshapeLoop {
     vf[1] = lead.v[1];
     // the iteration's scalar operands were prepared during the previous one
     const char *kt = kt_, *vt = vt_;
-    const unsigned k_dst = k_dst_, v_dst = v_dst_;
+    const unsigned k_dst = lds_addr_of(lds) + k_slot(PH + 3) + d.lds_w;
+    const unsigned v_dst = lds_addr_of(lds) + v_slot(PH + 1) + d.lds_w;
     const int cls_nxt = cls_nxt_, kb_nxt = kb1;
     const bool attend_cur = cls_cur != 0;
     // ... and the next one's are prepared in round 5, between MFMAs
     auto prepare_next = [&]() {
-      const unsigned r0 = ra; ra = rb; rb = rc; rc = r0;
       kb1 = kb2; kb2 = kb3;
       if (ti3 + 1 < T) {
         ++ti3;
@@ -847,14 +853,14 @@ struct AshapeLoop {
         sum_pair(8 * r + 4 + 2 * g);
         if (r == 7 && g == 1) finish_pair(62);
         // the first operands of the next iteration (its tiles were confirmed at this iteration's barrier)
-        if (r == 7 && g == 0) read_lead(lead);
+        if (r == 7 && g == 0) read_lead<(PH + 1) & 3, false>(lead);
         __builtin_amdgcn_sched_barrier(0);
       }
       if (r == 3) {
         // The iteration's one barrier sits in its middle.  Landed and visible behind it: the loads
         // issued in rounds 4..7 of the iteration before, K(t+2) and V(t), which the next iteration
-        // reads.  Free behind it: the slots of K(t) and V(t-2), last read in the iteration before,
-        // which this iteration's loads (rounds 4..7) overwrite.
+        // reads.  Free behind it: the slots this iteration's loads (rounds 4..7) overwrite, which
+        // held K(t-1) and V(t-3), last read two and three iterations ago.
         MINF_WAIT_VMCNT(0);
         __syncthreads();
       }
@@ -888,7 +894,6 @@ __device__ inline void ashape_pass_pipelined(const AshapeCtx &c, const WaveDma &
   AshapeLoop<ROWS256> lp{st, qa, lo, mp, d};
   lp.cls.init(mp);
   lp.c_log2 = c.c_log2; lp.lane = lane; lp.T = c.T; lp.T1 = c.T1; lp.s2 = c.s2; lp.lds = c.lds;
-  lp.ra = 0; lp.rb = TILE_BYTES; lp.rc = 2 * TILE_BYTES;
   lp.has_ref = false;
   const int last = c.T - 1;
   const int kb0 = lp.tile_base(0);
@@ -919,13 +924,20 @@ __device__ inline void ashape_pass_pipelined(const AshapeCtx &c, const WaveDma &
   __syncthreads();   // all waves are done with K(0) before iteration 0 overwrites it with K(3)
   lp.prepare(0);
   typename AshapeLoop<ROWS256>::Lead lead;
-  lp.read_lead(lead);
-  int t = 0;
-  for (; t + 1 <= c.T; t += 2) {
-    lp.iter(t, sa, sb, pa, pb, lead);
-    lp.iter(t + 1, sb, sa, pb, pa, lead);
+  lp.template read_lead<0, true>(lead);
+  // iterations t = 0 .. T (the last one finishes the output update of tile T-1); T is the same
+  // for the four waves, which meet at the barrier of every iteration
+  lp.template iter<0, true>(0, sa, sb, pa, pb, lead);
+  for (int t = 1; t <= c.T;) {
+    lp.template iter<1, false>(t, sb, sa, pb, pa, lead);
+    if (++t > c.T) break;
+    lp.template iter<2, false>(t, sa, sb, pa, pb, lead);
+    if (++t > c.T) break;
+    lp.template iter<3, false>(t, sb, sa, pb, pa, lead);
+    if (++t > c.T) break;
+    lp.template iter<0, false>(t, sa, sb, pa, pb, lead);
+    ++t;
   }
-  if (t <= c.T) lp.iter(t, sa, sb, pa, pb, lead);
   MINF_WAIT_VMCNT(0);   // the repeated loads of the last iterations
   __syncthreads();
 }
@@ -1912,7 +1924,7 @@ static hipError_t set_lds(const void *fn, size_t bytes) {
 hipError_t launch_ashape(const QKV &x, const HeadList &hl, int n_init, int n_local, hipStream_t st) {
   const int NB = x.N / BQ, NSB = (NB + 3) / 4;
   const Sched s = make_sched(hl, x.group, NSB);
-  const size_t lds = 6 * TILE_BYTES;   // three K and three V buffers
+  const size_t lds = 8 * TILE_BYTES;   // four K and four V slots
   // rows 256 bytes apart in both K and V (the [head][token][128] layout): cheaper tile fetch
   const bool rows256 = x.k_st == D && x.v_st == D;
   const void *fn = rows256 ? reinterpret_cast<const void *>(ashape_kernel<true>)
