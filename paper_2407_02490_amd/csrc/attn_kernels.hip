@@ -42,8 +42,8 @@
 //    in accumulator registers, scalar bookkeeping between MFMAs, constant
 //    wait counts.
 //  * A-shape / dense: a workgroup is 4 waves = 4 consecutive query blocks of
-//    one head; 64-key K/V tiles go through three-deep LDS rings shared by the
-//    4 waves.  Block-Sparse / Vertical-Slash: tile lists differ per query
+//    one head; 64-key K/V tiles go through LDS rings (four slots each, three
+//    tiles live) shared by the 4 waves.  Block-Sparse / Vertical-Slash: tile lists differ per query
 //    block, so a workgroup is a single wave that streams 32-key steps through
 //    private rings (2 K + 3 V slots, 40 KiB); 4 workgroups share a CU.
 #include <type_traits>
@@ -671,10 +671,11 @@ struct AshapeCls {
 //    the top of the round before (one wait per round); the wave's 8 tile loads
 //    go out one per round (back to back they stall the wave until the memory
 //    pipeline has taken them); scalar bookkeeping sits between the rounds' MFMAs.
-//  - K and V each cycle through three LDS buffers; iteration t issues the loads
-//    of K(t+3) and V(t+1) in its rounds 4..7 and reads K(t+1) and V(t-1).  Slot
-//    of tile i: i mod 3.  Past the last tile the loads repeat it into the free
-//    slot, so that every iteration issues 8 loads.
+//  - K and V each cycle through four LDS slots of which three hold live tiles;
+//    iteration t issues the loads of K(t+3) and V(t+1) in its rounds 4..7 and
+//    reads K(t+1) and V(t-1).  Slot of tile i: i mod 4; the loop is unrolled four
+//    times, so every slot address is an immediate.  Past the last tile the loads
+//    repeat it into the free slot, so that every iteration issues 8 loads.
 //  - The one barrier of an iteration sits after round 3 (with a wait for the
 //    loads of the iteration before).  The tiles the next iteration reads are
 //    therefore confirmed half an iteration early, and its first operands are
