@@ -140,7 +140,9 @@ minf_status minf_build_vs_index(const minf_qkv *x, const int32_t *heads, int32_t
  * Alg. 3, index part.  Mean-pools Q and K over 64-token blocks (fp32), forms
  * the block logits Q_hat K_hat^T / sqrt(d) for c <= b in fp32 and keeps, per
  * query block, the min(topk, b+1) largest (softmax is monotone per row, so
- * it is not applied).  topk >= 1; block must be 64.
+ * it is not applied).  topk >= 1; block must be 64.  If out->order is not
+ * NULL it receives the processing order of the query blocks (see
+ * minf_bs_index).
  */
 minf_status minf_build_bs_index(const minf_qkv *x, const int32_t *heads, int32_t n_heads,
                                 int32_t block, int32_t topk, minf_bs_index *out,
@@ -157,7 +159,7 @@ minf_status minf_ashape_attn(const minf_qkv *x, const int32_t *heads, int32_t n_
 /*
  * Vertical-Slash attention (Alg. 2 last steps, Alg. 5): per 64-row query block
  * the keys of the slash runs, then the kept verticals that are causal and not
- * already inside a run, gathered 64 at a time.  Every permitted key is
+ * already inside a run, gathered into dense steps.  Every permitted key is
  * attended exactly once; a row with no permitted key gives zeros.
  * Row r of idx belongs to heads[r].
  */
