@@ -43,9 +43,11 @@
 //    wait counts.
 //  * A-shape / dense: a workgroup is 4 waves = 4 consecutive query blocks of
 //    one head; 64-key K/V tiles go through LDS rings (four slots each, three
-//    tiles live) shared by the 4 waves.  Block-Sparse / Vertical-Slash: tile lists differ per query
-//    block, so a workgroup is a single wave that streams 32-key steps through
-//    private rings (2 K + 3 V slots, 40 KiB); 4 workgroups share a CU.
+//    tiles live) shared by the 4 waves.  Block-Sparse / Vertical-Slash: tile
+//    lists differ per query block, so a workgroup is a single wave that streams
+//    32-key steps through private rings (2 K + 3 V slots, 40 KiB); 4 workgroups
+//    share a CU.  Both loops are unrolled over their rings (4x and 6x), so that
+//    every LDS slot address is an immediate.
 #include <type_traits>
 
 #include "mfma_tile.h"
