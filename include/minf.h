@@ -16,9 +16,10 @@
  *     enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = the
  *     default stream).  Index structs written by minf_build_* may be consumed
  *     by the attention calls on the same stream without a host round trip.
- *   - Arguments are validated on the host before anything is enqueued; a
- *     status other than MINF_OK means nothing was launched (MINF_ERR_HIP: a
- *     launch was refused by the runtime).
+ *   - Arguments are validated on the host before anything is enqueued: with
+ *     any status other than MINF_OK and MINF_ERR_HIP nothing was launched.
+ *     MINF_ERR_HIP means the runtime refused a launch; with batch > 1 the
+ *     launches of earlier batch elements may already be enqueued then.
  *   - Layout: q [batch, n_q_heads, seq_len, head_dim], k/v [batch, n_kv_heads,
  *     seq_len, head_dim], o like q; bf16; head_dim contiguous; strides in
  *     elements for (batch, head, token).  Query head h reads KV head
@@ -137,6 +138,20 @@ minf_status minf_build_vs_index(const minf_qkv *x, const int32_t *heads, int32_t
                                 void *hip_stream);
 
 /*
+ * The "sparseformat" step alone (Alg. 2; Alg. 4's role, App. C.4.2) for lines
+ * the caller chose: the static-index use of the attention call (Section 4,
+ * ablation "Ours w/ static").  On entry, for every row r < rows of idx:
+ * v_idx[r, 0 .. n_v) holds the kept vertical positions and s_idx[r, 0 .. n_s)
+ * the kept slash offsets, both ascending, distinct and inside [0, seq_len),
+ * with counts[r] = {n_v, n_s, *, *} (device memory, n_v <= idx->nv,
+ * n_s <= idx->ns).  Fills cover, cover_bits and counts[r][2..3] on the stream;
+ * v_idx and s_idx are left as they are.  Offsets outside [0, seq_len) are
+ * clamped into it.
+ */
+minf_status minf_vs_index_from_lines(int32_t seq_len, int32_t rows, minf_vs_index *idx,
+                                     void *hip_stream);
+
+/*
  * Alg. 3, index part.  Mean-pools Q and K over 64-token blocks (fp32), forms
  * the block logits Q_hat K_hat^T / sqrt(d) for c <= b in fp32 and keeps, per
  * query block, the min(topk, b+1) largest (softmax is monotone per row, so
@@ -161,7 +176,10 @@ minf_status minf_ashape_attn(const minf_qkv *x, const int32_t *heads, int32_t n_
  * the keys of the slash runs, then the kept verticals that are causal and not
  * already inside a run, gathered into dense steps.  Every permitted key is
  * attended exactly once; a row with no permitted key gives zeros.
- * Row r of idx belongs to heads[r].
+ * Row r of idx belongs to heads[r].  The gathered verticals are addressed with
+ * 32-bit byte offsets: seq_len * k_stride[2] * 2 and seq_len * v_stride[2] * 2
+ * must be below 2^32 (MINF_ERR_SHAPE otherwise; e.g. a fused token-major QKV
+ * buffer of 1M tokens with 16 or more heads per token is refused).
  */
 minf_status minf_vs_attn(const minf_qkv *x, const int32_t *heads, int32_t n_heads,
                          const minf_vs_index *idx, void *hip_stream);

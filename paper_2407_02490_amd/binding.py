@@ -13,7 +13,7 @@ import torch
 __all__ = [
     "lib", "MinfError", "VSIndex", "BSIndex", "alloc_vs_index", "alloc_bs_index",
     "vs_index_from_host", "bs_index_from_host",
-    "minf_build_vs_index", "minf_build_bs_index", "minf_ashape_attn", "minf_vs_attn",
+    "minf_build_vs_index", "minf_vs_index_from_lines", "minf_build_bs_index", "minf_ashape_attn", "minf_vs_attn",
     "minf_bs_attn", "minf_dense_attn", "minf_vs_cover_words",
     "minf_vs_index_workspace_bytes", "minf_bs_index_workspace_bytes",
 ]
@@ -73,6 +73,8 @@ def lib():
     L.minf_bs_index_workspace_bytes.argtypes = [pq, i32]
     L.minf_build_vs_index.restype = ctypes.c_int
     L.minf_build_vs_index.argtypes = [pq, pi, i32, i32, i32, i32, i32, ctypes.POINTER(_VSIndex), vp, sz, vp]
+    L.minf_vs_index_from_lines.restype = ctypes.c_int
+    L.minf_vs_index_from_lines.argtypes = [i32, i32, ctypes.POINTER(_VSIndex), vp]
     L.minf_build_bs_index.restype = ctypes.c_int
     L.minf_build_bs_index.argtypes = [pq, pi, i32, i32, i32, ctypes.POINTER(_BSIndex), vp, sz, vp]
     L.minf_ashape_attn.restype = ctypes.c_int
@@ -176,41 +178,27 @@ def alloc_bs_index(rows, seq_len, topk, device="cuda"):
     return BSIndex(rows, seq_len // BLOCK, topk, device)
 
 
-def vs_index_from_host(v_lists, s_lists, seq_len, device="cuda"):
+def vs_index_from_host(v_lists, s_lists, seq_len, device="cuda", stream=None):
     """Index buffers filled from host lists of vertical positions and slash
-    offsets (one pair per head): the "static index" use of the attention call.
-    Builds the merged offset runs and the run bitmap the kernels expect."""
+    offsets (one pair per head, each ascending and distinct): the "static
+    index" use of the attention call.  The lists are copied to the device as
+    they are; minf_vs_index_from_lines builds the merged offset runs and the
+    run bitmap there."""
     rows = len(v_lists)
     nv = max(1, max(len(v) for v in v_lists))
     ns = max(1, max(len(s) for s in s_lists))
     idx = VSIndex(rows, nv, ns, seq_len, device)
     v_idx = np.zeros((rows, nv), np.int32)
     s_idx = np.zeros((rows, ns), np.int32)
-    cover = np.zeros((rows, ns, 2), np.int32)
-    bits = np.zeros((rows, idx.cover_words), np.uint32)
     counts = np.zeros((rows, 4), np.int32)
     for r in range(rows):
-        v = np.unique(np.asarray(v_lists[r], dtype=np.int64))
-        s = np.unique(np.asarray(s_lists[r], dtype=np.int64))
-        v_idx[r, :v.size], s_idx[r, :s.size] = v, s
-        n_c = 0
-        if s.size:
-            brk = np.flatnonzero(np.diff(s) > BLOCK)          # a gap wider than a tile starts a new run
-            first = np.concatenate([[0], brk + 1])
-            last = np.concatenate([brk, [s.size - 1]])
-            n_c = first.size
-            cover[r, :n_c, 0] = s[first] - BLOCK + 1
-            cover[r, :n_c, 1] = s[last] + 1
-            flat = np.zeros(idx.cover_words * 32, np.uint8)
-            for t0, t1 in cover[r, :n_c]:
-                flat[t0 + BLOCK:t1 + BLOCK] = 1
-            bits[r] = np.packbits(flat, bitorder="little").view(np.uint32)
-        counts[r, :3] = (v.size, s.size, n_c)
+        v_idx[r, :len(v_lists[r])] = v_lists[r]
+        s_idx[r, :len(s_lists[r])] = s_lists[r]
+        counts[r, :2] = (len(v_lists[r]), len(s_lists[r]))
     idx.v_idx.copy_(torch.from_numpy(v_idx))
     idx.s_idx.copy_(torch.from_numpy(s_idx))
-    idx.cover.copy_(torch.from_numpy(cover))
-    idx.cover_bits.copy_(torch.from_numpy(bits.view(np.int32)))
     idx.counts.copy_(torch.from_numpy(counts))
+    minf_vs_index_from_lines(idx, stream=stream)
     return idx
 
 
@@ -250,6 +238,11 @@ def minf_build_vs_index(q, k, heads, last_q, nv, ns, out, ws, block=BLOCK, scale
     _check(lib().minf_build_vs_index(ctypes.byref(x), h, n, last_q, nv, ns, block, ctypes.byref(s),
                                      ctypes.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size(),
                                      _stream(stream)))
+
+
+def minf_vs_index_from_lines(idx, stream=None):
+    s = idx.c_struct()
+    _check(lib().minf_vs_index_from_lines(idx.seq_len, idx.rows, ctypes.byref(s), _stream(stream)))
 
 
 def minf_build_bs_index(q, k, heads, topk, out, ws, block=BLOCK, scale=0.0, stream=None):

@@ -48,9 +48,12 @@
 //    32-key steps through private rings (2 K + 3 V slots, 40 KiB); 4 workgroups
 //    share a CU.  Both loops are unrolled over their rings (4x and 6x), so that
 //    every LDS slot address is an immediate.
+#include <stdlib.h>
+#include <string.h>
 #include <type_traits>
 
 #include "mfma_tile.h"
+#include "vs_ring_sched.h"
 
 namespace minf {
 
@@ -999,6 +1002,16 @@ __global__ __launch_bounds__(256) void ashape_kernel(QKV x, HeadList hl, int n_i
   if (active) wave_finish(st, oh, x.o_st, q0, lds + wave * TILE_BYTES, lane);
 }
 
+// Makes LDS writes of this wave's lanes visible to its other lanes.  LDS operations of one wave
+// execute in issue order; the fences only keep the compiler from reordering them.  (The column
+// lists of the Vertical-Slash kernels are private to a wave, and the waves of a workgroup walk
+// lists of different lengths, so no workgroup barrier may be used there.)
+__device__ inline void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // ---------------------------------------------------------------------------
 // Single-wave kernels: 32-key steps through private rings.
 // LDS: 2 K slots + 3 V slots of 8 KiB = 40 KiB (the column list of the
@@ -1755,7 +1768,7 @@ __device__ inline void vs_pass(const VsCtx &c, WaveState &st, const LaneOfs &lo,
     if (ncol == 0) continue;
     const int nstep = (ncol + 31) / 32;
     if (lane + ncol < nstep * 32) cols[ncol + lane] = KEY_NONE;   // pad the last step
-    __syncthreads();                   // cols[] visible to every lane; earlier vector loads drained
+    wave_lds_sync();                   // cols[] visible to every lane (earlier tile loads were awaited)
     fetch_step<false>(c.buf, s, c.kh, c.vh, c.k_st, c.v_st, 0, cols, c.N, lane);
     for (int t = 0; t < nstep; ++t) {
       if (t + 1 < nstep) {
@@ -1767,7 +1780,7 @@ __device__ inline void vs_pass(const VsCtx &c, WaveState &st, const LaneOfs &lo,
       gathered_step<1, PASS>(st, has_ref, lo, c.buf.k(s), c.buf.v(s), cols + t * 32, mp, c.c_log2, lane);
       s ^= 1;
     }
-    __syncthreads();                   // every lane is done with cols[] before the next round refills it
+    wave_lds_sync();                   // every lane is done with cols[] before the next round refills it
   }
 }
 
@@ -1814,6 +1827,47 @@ struct VsColGen {
   }
 };
 
+// Phase B of the optimistic pass: the kept verticals that are causal for the block and outside
+// every run, compacted into this wave's column list and gathered 32 per step through this wave's
+// own ring.  No workgroup barrier: every wave has its own list length.
+template <bool ROWS256>
+__device__ inline void vs_cols_pipelined(const VsCtx &c, WaveState &st, const QAcc &qa, bool &has_ref,
+                                         const LaneOfs &lo, const MaskP &mp, const DmaLane &dk,
+                                         const DmaLane &dv, int lane) {
+  const int q0 = c.q0;
+  const char *khb = reinterpret_cast<const char *>(c.kh), *vhb = reinterpret_cast<const char *>(c.vh);
+  const unsigned k_rb = (unsigned)c.k_st * 2u, v_rb = (unsigned)c.v_st * 2u;
+  const int qlast = q0 + BQ - 1;
+  int *cols = c.cols;
+  int vpos = 0;
+  while (vpos < c.n_v) {
+    int ncol = 0;
+    while (vpos < c.n_v && ncol <= VCAP - 64) {
+      const int i = vpos + lane;
+      const int v = i < c.n_v ? c.vlist[i] : KEY_NONE;
+      bool ok = v <= qlast && v >= 0;
+      if (ok) {
+        const int t = q0 - v + 64;     // bit index of offset q0 - v, in [1, q0 + 64]
+        ok = ((c.bits[t >> 5] >> (t & 31)) & 1u) == 0u;
+      }
+      const unsigned long long bal = __builtin_amdgcn_ballot_w64(ok);
+      const int before = __builtin_popcountll(bal & ((1ull << lane) - 1ull));
+      if (ok) cols[ncol + before] = v;
+      ncol += __builtin_popcountll(bal);
+      vpos += 64;
+      if (__shfl(v, 0) > qlast) { vpos = c.n_v; break; }
+    }
+    if (ncol == 0) continue;
+    const int nstep = (ncol + 31) / 32;
+    if (lane + ncol < nstep * 32) cols[ncol + lane] = KEY_NONE;   // pad the last step
+    wave_lds_sync();
+    VsColGen gen{cols, nstep, q0, 0};
+    WavePipe<VsColGen, true, ROWS256> pipe{gen, st, qa, has_ref, lo, c.buf, khb, vhb, k_rb, v_rb, dk, dv, c.N, mp, c.c_log2, lane};
+    pipe.run();
+    wave_lds_sync();
+  }
+}
+
 // Optimistic pass of the Vertical-Slash kernel, software pipelined.
 template <bool ROWS256>
 __device__ inline void vs_pass_pipelined(const VsCtx &c, WaveState &st, const LaneOfs &lo, const MaskP &mp,
@@ -1840,36 +1894,7 @@ __device__ inline void vs_pass_pipelined(const VsCtx &c, WaveState &st, const La
     pipe.run();
     if (usable < n) break;
   }
-  // ---- phase B: verticals
-  const int qlast = q0 + BQ - 1;
-  int *cols = c.cols;
-  int vpos = 0;
-  while (vpos < c.n_v) {
-    int ncol = 0;
-    while (vpos < c.n_v && ncol <= VCAP - 64) {
-      const int i = vpos + lane;
-      const int v = i < c.n_v ? c.vlist[i] : KEY_NONE;
-      bool ok = v <= qlast && v >= 0;
-      if (ok) {
-        const int t = q0 - v + 64;     // bit index of offset q0 - v, in [1, q0 + 64]
-        ok = ((c.bits[t >> 5] >> (t & 31)) & 1u) == 0u;
-      }
-      const unsigned long long bal = __builtin_amdgcn_ballot_w64(ok);
-      const int before = __builtin_popcountll(bal & ((1ull << lane) - 1ull));
-      if (ok) cols[ncol + before] = v;
-      ncol += __builtin_popcountll(bal);
-      vpos += 64;
-      if (__shfl(v, 0) > qlast) { vpos = c.n_v; break; }
-    }
-    if (ncol == 0) continue;
-    const int nstep = (ncol + 31) / 32;
-    if (lane + ncol < nstep * 32) cols[ncol + lane] = KEY_NONE;   // pad the last step
-    __syncthreads();
-    VsColGen gen{cols, nstep, q0, 0};
-    WavePipe<VsColGen, true, ROWS256> pipe{gen, st, qa, has_ref, lo, c.buf, khb, vhb, k_rb, v_rb, dk, dv, c.N, mp, c.c_log2, lane};
-    pipe.run();
-    __syncthreads();
-  }
+  vs_cols_pipelined<ROWS256>(c, st, qa, has_ref, lo, mp, dk, dv, lane);
 }
 
 template <bool ROWS256>
@@ -1918,6 +1943,336 @@ __global__ __launch_bounds__(64) void vs_kernel(QKV x, HeadList hl, const int32_
 }
 
 // ---------------------------------------------------------------------------
+// Vertical-Slash, shared tiles: a workgroup is four waves = four consecutive
+// query blocks of one head.  The key sequence of a slash run is the same for
+// every query block up to a shift by the block's first row (App. C.4.2: the
+// slash tiles are translation invariant), so the four waves walk one common
+// schedule of 32-key steps, each wave two steps behind the one before it; waves
+// that are inside the same run then need the same 32 keys at the same moment
+// and only the first of them (the "leader") fetches them, into its own ring
+// (see vs_ring_sched.h).  Every wave still computes only its own tiles.
+// LDS: four rings of 2 K + 3 V slots of 8 KiB (160 KiB); ring slots are
+// indexed by the step number, which is common to the four waves.
+// ---------------------------------------------------------------------------
+constexpr int RING_BYTES = 5 * HALF_BYTES;
+
+// The runs of a head, 64 at a time one per lane; the next 64 are fetched when the schedule
+// reaches them (once per 64 runs; the load waits for the tile loads in flight).
+struct RunLanes {
+  const int2 *runs;
+  int n_c, lane, base;
+  int2 mine;
+  __device__ inline void load(int b) {
+    base = b;
+    mine = make_int2(KEY_NONE, KEY_NONE);
+    if (b + lane < n_c) mine = runs[b + lane];
+  }
+  __device__ inline bool operator()(int iv, int &a, int &b) {
+    if (iv >= n_c) return false;
+    if (iv - base >= 64) load(base + 64);
+    a = __builtin_amdgcn_readlane(mine.x, iv - base);
+    b = __builtin_amdgcn_readlane(mine.y, iv - base);
+    return true;
+  }
+};
+
+// The three-stream pipeline of WavePipe3 for four waves in lock step.  Differences:
+//  - the rows of a step live in the ring of the step's leader (RStep::src); a wave issues the
+//    tile loads of a step only if it is that leader (RStep::load);
+//  - one workgroup barrier at the top of every iteration, behind the wait for the wave's own
+//    loads: the leader's rows are then visible to its followers, and every wave is done reading
+//    the slots this iteration's loads overwrite;
+//  - a step with nothing to attend (the idle steps of the skew, steps of a run that lie
+//    before key 0 for this wave only) is run with P = 0.  The rings are zero-filled at the start
+//    and only ever receive K/V rows, so what such a step multiplies by zero is finite.
+template <class Gen, bool ROWS256>
+struct RingPipe3 {
+  Gen &gen;
+  WaveState &st;
+  const QAcc &qa;
+  bool &has_ref;
+  const LaneOfs &lo;
+  char *lds0;                // ring of wave w at lds0 + w * RING_BYTES
+  int wave;
+  const char *kh, *vh;       // head bases (bytes)
+  unsigned k_rb, v_rb;
+  const DmaLane &dk, &dv;
+  MaskP mp;
+  float c_log2;
+  int lane;
+  RStep d0, d1, d2;          // steps t (softmax), t+1 (logits), t+2 (K fetch)
+  bool h0, h1, h2, hp;       // ... exist; hp: step t-1 exists (its P awaits the output update)
+  int src_p;                 // ring that holds V of step t-1
+
+  static constexpr unsigned k_slot(int i) { return (unsigned)i * HALF_BYTES; }
+  static constexpr unsigned v_slot(int i) { return (unsigned)(2 + i) * HALF_BYTES; }
+  __device__ inline char *ring(int w) const { return lds0 + w * RING_BYTES; }
+  __device__ inline const char *row0(const char *head, unsigned rb, const RStep &d) const {
+    const unsigned kb = (unsigned)__builtin_amdgcn_readfirstlane(d.kbase);
+    return head + (uint64_t)kb * rb;
+  }
+  __device__ inline void barrier() const { asm volatile("s_barrier" ::: "memory"); }
+  // element mask and / or exponent reference on the fresh logits of a step (nothing for a step
+  // without work: its logits are never used)
+  __device__ inline void fresh(f32x16 (&s)[1][2], const RStep &d) {
+    if (d.mask || (d.work && !has_ref)) {
+      MaskP m = mp;
+      m.lo = d.lo; m.hi = d.hi;
+      if (d.mask) window_mask<1>(s, d.kbase, m, lane);
+      if (!has_ref) special_tile<1>(s, st, d.kbase, m, false, true, c_log2, lane);
+    }
+    has_ref = has_ref || d.work;
+  }
+  __device__ inline void qk_first(f32x16 (&s)[1][2], const char *tK) const {
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+      const bf16x8 a = lds_read_k(tK, lo.k[ks]);
+      if (ks == 0) {
+        mfma_qk_first(s[0][0], a, qa.q[0][0]);
+        mfma_qk_first(s[0][1], a, qa.q[1][0]);
+      } else {
+        mfma_qk_acc(s[0][0], a, qa.q[0][ks]);
+        mfma_qk_acc(s[0][1], a, qa.q[1][ks]);
+      }
+    }
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");   // results readable by the vector ALU
+  }
+  template <bool IS_K>
+  __device__ inline void fetch_whole(const RStep &d, unsigned dst) const {
+    const char *a = row0(IS_K ? kh : vh, IS_K ? k_rb : v_rb, d);
+    const unsigned rb = IS_K ? k_rb : v_rb;
+    const unsigned (&vo)[4] = IS_K ? dk.voff : dv.voff;
+    dma_pair<ROWS256, 0>(a, rb, vo, dst); dma_pair<ROWS256, 2>(a, rb, vo, dst);
+    dma_pair<ROWS256, 4>(a, rb, vo, dst); dma_pair<ROWS256, 6>(a, rb, vo, dst);
+  }
+
+  // Iteration t with PH = t mod 6: K of step s lives in K slot s mod 2, V of step s in V slot
+  // (s + 1) mod 3 of the leader's ring.
+  template <int PH, bool FIRST>
+  __device__ inline void iter(f32x16 (&s_cur)[1][2], f32x16 (&s_nxt)[1][2], bf16x8 (&p_prev)[2][2],
+                              bf16x8 (&p_cur)[2][2]) {
+    // Outstanding loads of this wave: K of step t+1, then V of step t (eight each, if this wave
+    // leads those steps).  K must have landed, and so must V of step t-1 (older than both).
+    if (h0 && d0.load) MINF_WAIT_VMCNT(8); else MINF_WAIT_VMCNT(0);
+    barrier();
+    const char *tK = ring(d1.src) + k_slot((PH + 1) & 1);
+    // V(t-1); in the very first iteration there is no step -1: zero P times the rows of V(0)
+    const char *tV = ring(FIRST ? d0.src : src_p) + v_slot(FIRST ? 1 : PH % 3);
+    const unsigned k_dst = lds_addr_of(ring(wave)) + k_slot(PH & 1);
+    const unsigned v_dst = lds_addr_of(ring(wave)) + v_slot((PH + 2) % 3);
+    const bool ld_k = h2 && d2.load, ld_v = h1 && d1.load;
+    const char *kt = row0(kh, k_rb, d2), *vt = row0(vh, v_rb, d1);
+    bf16x8 kf[8], vf[8];
+    kf[0] = lds_read_k(tK, lo.k[0]);
+    auto fetch_v = [&](int i) {            // output update step i = (t, db)
+      const int base = 16 * (i >> 2) * ROW_BYTES, db = i & 3;
+      return lds_read_vt(tV, lo.v[db][0] + base, lo.v[db][1] + base);
+    };
+    vf[0] = fetch_v(0);
+    const bool attend = h0 && d0.work;
+    // nothing to attend: infinite reference, P = exp2(-inf) = 0
+    const float m0 = attend ? st.m[0] : INFINITY, m1 = attend ? st.m[1] : INFINITY;
+    float lsum0 = 0.f, lsum1 = 0.f;
+    float pe0 = 0.f, pe1 = 0.f;
+    auto finish_pair = [&](int e) {        // pair e's exponentials are in pe0, pe1
+      const int tt = e >> 3, nb = (e >> 2) & 1;
+      if (nb == 0) lsum0 += pe0 + pe1; else lsum1 += pe0 + pe1;
+      const f32x2 two = {pe0, pe1};
+      unsigned pk = __builtin_bit_cast(unsigned, __builtin_convertvector(two, bf16x2));
+      asm volatile("" : "+v"(pk), "+v"(lsum0), "+v"(lsum1));
+      const bf16x2 b2 = __builtin_bit_cast(bf16x2, pk);
+      p_cur[nb][tt][2 * (e & 3)] = b2[0];
+      p_cur[nb][tt][2 * (e & 3) + 1] = b2[1];
+    };
+    float ne0 = 0.f, ne1 = 0.f;
+    auto exp_pair = [&](int e) {
+      const int tt = e >> 3, nb = (e >> 2) & 1, r = 8 * tt + 2 * (e & 3);
+      const float m_use = nb == 0 ? m0 : m1;
+      ne0 = fast_exp2(fmaf(s_cur[0][nb][r], c_log2, -m_use));
+      ne1 = fast_exp2(fmaf(s_cur[0][nb][r + 1], c_log2, -m_use));
+      asm volatile("" : "+v"(ne0), "+v"(ne1));
+    };
+    auto sum_pair = [&](int e) {           // finishes pair e - 1, then pair e's exponentials take its place
+      if (e > 0) finish_pair(e - 1);
+      pe0 = ne0; pe1 = ne1;
+    };
+    // the round structure is that of WavePipe3: four groups, each opened by one MFMA
+    auto round = [&](auto rc_) {
+      constexpr int r = decltype(rc_)::value;
+      if (r == 0) mfma_qk_first(s_nxt[0][0], kf[0], qa.q[0][0]);
+      else mfma_qk_acc(s_nxt[0][0], kf[r], qa.q[0][r]);
+      exp_pair(2 * r);
+      if (r + 1 < 8) kf[(r + 1) & 7] = lds_read_k(tK, lo.k[(r + 1) & 7]);
+      __builtin_amdgcn_sched_barrier(0);
+      if (r == 0) mfma_qk_first(s_nxt[0][1], kf[0], qa.q[1][0]);
+      else mfma_qk_acc(s_nxt[0][1], kf[r], qa.q[1][r]);
+      sum_pair(2 * r);
+      if (r < 4) {
+        if (ld_k) dma_pair<ROWS256, 2 * (r & 3)>(kt, k_rb, dk.voff, k_dst);
+      } else {
+        if (ld_v) dma_pair<ROWS256, 2 * (r & 3)>(vt, v_rb, dv.voff, v_dst);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      {
+        const int tt = r >> 2, db = r & 3;
+        st.o[db][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[r], p_prev[0][tt], st.o[db][0], 0, 0, 0);
+      }
+      exp_pair(2 * r + 1);
+      if (r + 1 < 8) vf[(r + 1) & 7] = fetch_v((r + 1) & 7);
+      __builtin_amdgcn_sched_barrier(0);
+      {
+        const int tt = r >> 2, db = r & 3;
+        st.o[db][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[r], p_prev[1][tt], st.o[db][1], 0, 0, 0);
+      }
+      sum_pair(2 * r + 1);
+      if (r == 7) finish_pair(15);
+      if (r == 3) {
+        // advance the generator between MFMAs
+        hp = h0;
+        src_p = d0.src;
+        d0 = d1; d1 = d2;
+        h0 = h1; h1 = h2;
+        RStep dn = d2;
+        h2 = h2 && gen.next(dn);
+        if (h2) d2 = dn;
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    round(std::integral_constant<int, 0>{});
+    round(std::integral_constant<int, 1>{});
+    round(std::integral_constant<int, 2>{});
+    round(std::integral_constant<int, 3>{});
+    round(std::integral_constant<int, 4>{});
+    round(std::integral_constant<int, 5>{});
+    round(std::integral_constant<int, 6>{});
+    round(std::integral_constant<int, 7>{});
+    if (attend) {
+      st.l[0] += lsum0;
+      st.l[1] += lsum1;
+    }
+    // after the generator advanced in round 3: d0 = the step whose logits are now in s_nxt
+    if (h0) fresh(s_nxt, d0);
+  }
+  // Every wave of the workgroup must call this, and the generators of the four waves must yield
+  // the same number of steps: the iterations meet at barriers.
+  __device__ inline void run() {
+    h0 = gen.next(d0);
+    if (!h0) return;
+    d1 = d0;
+    h1 = gen.next(d1);
+    d2 = d1;
+    h2 = h1 && gen.next(d2);
+    hp = false;
+    src_p = wave;
+    // K of steps 0, 1 into K slots 0, 1; V of step 0 into V slot 1 (leaders only)
+    if (d0.load) fetch_whole<true>(d0, lds_addr_of(ring(wave)) + k_slot(0));
+    if (h1 && d1.load) fetch_whole<true>(d1, lds_addr_of(ring(wave)) + k_slot(1));
+    if (d0.load) fetch_whole<false>(d0, lds_addr_of(ring(wave)) + v_slot(1));
+    MINF_WAIT_VMCNT(0);
+    barrier();
+    f32x16 sa[1][2], sb[1][2];
+    bf16x8 pa[2][2], pb[2][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) (&pa[0][0])[i][j] = (__bf16)0.f;
+    qk_first(sa, ring(d0.src) + k_slot(0));
+    fresh(sa, d0);
+    iter<0, true>(sa, sb, pa, pb);
+    while (h0 || hp) {
+      iter<1, false>(sb, sa, pb, pa);
+      if (!(h0 || hp)) break;
+      iter<2, false>(sa, sb, pa, pb);
+      if (!(h0 || hp)) break;
+      iter<3, false>(sb, sa, pb, pa);
+      if (!(h0 || hp)) break;
+      iter<4, false>(sa, sb, pa, pb);
+      if (!(h0 || hp)) break;
+      iter<5, false>(sb, sa, pb, pa);
+      if (!(h0 || hp)) break;
+      iter<0, false>(sa, sb, pa, pb);
+    }
+    MINF_WAIT_VMCNT(0);
+    barrier();               // the followers are done with this wave's ring
+  }
+};
+
+template <bool ROWS256>
+__global__ __launch_bounds__(256) void vs_ring_kernel(QKV x, HeadList hl, const int32_t *v_idx,
+                                                      const int32_t *cover, const uint32_t *cover_bits,
+                                                      const int32_t *counts, int nv, int ns, int cover_words,
+                                                      Sched sched) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const int NB = x.N / BQ;
+  int slot, sb;
+  if (!decode_wg(sched, slot, sb)) return;
+  const int head = __builtin_amdgcn_readfirstlane(hl.h[slot]);
+  const int kvh = to_sgpr(head / x.group);
+  const bf16_t *qh = x.q + head * x.q_sh;
+  bf16_t *oh = x.o + head * x.o_sh;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int blk = sb * 4 + wave;
+  // A wave past the last block runs the common schedule on the rows of the last block (the
+  // barriers need it) with the masks of its virtual position; it writes nothing.
+  const bool active = blk < NB;
+  const int q0 = blk * BQ;
+  char *ring = lds + wave * RING_BYTES;
+
+  // rings start as zeros: a step that attends nothing multiplies their content by P = 0
+#pragma unroll
+  for (int i = 0; i < RING_BYTES / (64 * 16); ++i)
+    *reinterpret_cast<uint4 *>(ring + (i * 64 + lane) * 16) = make_uint4(0u, 0u, 0u, 0u);
+
+  VsCtx c;
+  c.kh = x.k + kvh * x.k_sh; c.vh = x.v + kvh * x.v_sh; c.k_st = x.k_st; c.v_st = x.v_st;
+  c.N = x.N; c.q0 = q0; c.buf = StepBuf{ring}; c.c_log2 = x.c_log2;
+  c.cols = reinterpret_cast<int *>(ring + 4 * HALF_BYTES);   // [VCAP + 64], third V slot
+  c.n_v = min(max(counts[slot * 4 + 0], 0), nv);
+  c.n_c = min(max(counts[slot * 4 + 2], 0), ns);
+  c.vlist = v_idx + (int64_t)slot * nv;
+  c.runs = reinterpret_cast<const int2 *>(cover) + (int64_t)slot * ns;
+  c.bits = cover_bits + (int64_t)slot * cover_words;
+
+  WaveState st;
+  wave_init(st, qh, x.q_st, active ? q0 : (NB - 1) * BQ, lane);
+  LaneOfs lo;
+  lane_offsets(lo, lane);
+  MaskP mp;
+  mp.q0 = q0; mp.n_init = KEY_NONE; mp.n_local = 1; mp.lo = 0; mp.hi = 0;
+  __syncthreads();
+
+  bool has_ref = false;
+  QAcc qa;
+  pin_q(qa, st);
+  DmaLane dk, dv;
+  dma_lane_init(dk, c.k_st, lane);
+  dma_lane_init(dv, c.v_st, lane);
+  {
+    // ---- phase A: slash runs, shared between the four waves
+    RunLanes rl{c.runs, c.n_c, lane, 0, make_int2(KEY_NONE, KEY_NONE)};
+    rl.load(0);
+    VsRingGen<RunLanes> gen(rl, sb * 4 * BQ, wave, c.N);
+    RingPipe3<VsRingGen<RunLanes>, ROWS256> pipe{gen, st, qa, has_ref, lo, lds, wave,
+                                                 reinterpret_cast<const char *>(c.kh),
+                                                 reinterpret_cast<const char *>(c.vh), (unsigned)c.k_st * 2u,
+                                                 (unsigned)c.v_st * 2u, dk, dv, mp, c.c_log2, lane};
+    pipe.run();
+  }
+  if (!active) return;       // no workgroup barrier below this line
+  // ---- phase B: verticals, per wave
+  vs_cols_pipelined<ROWS256>(c, st, qa, has_ref, lo, mp, dk, dv, lane);
+  if (needs_exact(st)) {
+    load_q(st, qh, x.q_st, q0, lane);   // the pipelined pass kept Q in accumulator registers only
+    reset_for_max_pass(st);
+    vs_pass<PASS_MAX>(c, st, lo, mp, lane);
+    finish_max_pass(st, x.c_log2);
+    vs_pass<PASS_FIX>(c, st, lo, mp, lane);
+  }
+  wave_finish(st, oh, x.o_st, q0, ring, lane);
+}
+
+// ---------------------------------------------------------------------------
 // host-side launches
 // ---------------------------------------------------------------------------
 static hipError_t set_lds(const void *fn, size_t bytes) {
@@ -1962,12 +2317,29 @@ hipError_t launch_vs(const QKV &x, const HeadList &hl, const int32_t *v_idx, con
                      const uint32_t *cover_bits, const int32_t *counts, int nv, int ns,
                      int cover_words, hipStream_t st) {
   const int NB = x.N / BQ;
+  // gathered rows are addressed with 32-bit byte offsets from the head base (checked by the caller)
+  const bool rows256 = x.k_st == D && x.v_st == D;
+  // MINF_VS_ENGINE=ring selects the shared-tile engine (four waves per workgroup, slash-run tiles
+  // fetched once per group of waves); it is slower than the default on every measured workload
+  // and kept as a measured alternative.
+  const bool use_ring = getenv("MINF_VS_ENGINE") != nullptr && strcmp(getenv("MINF_VS_ENGINE"), "ring") == 0;
+  if (use_ring) {
+    const Sched s = make_sched(hl, x.group, (NB + 3) / 4);
+    const size_t lds = 4 * RING_BYTES;
+    const void *fn = rows256 ? reinterpret_cast<const void *>(vs_ring_kernel<true>)
+                             : reinterpret_cast<const void *>(vs_ring_kernel<false>);
+    hipError_t e = set_lds(fn, lds);
+    if (e != hipSuccess) return e;
+    if (rows256)
+      hipLaunchKernelGGL(vs_ring_kernel<true>, dim3(s.per_xcd * 8), dim3(256), lds, st, x, hl, v_idx, cover,
+                         cover_bits, counts, nv, ns, cover_words, s);
+    else
+      hipLaunchKernelGGL(vs_ring_kernel<false>, dim3(s.per_xcd * 8), dim3(256), lds, st, x, hl, v_idx, cover,
+                         cover_bits, counts, nv, ns, cover_words, s);
+    return hipGetLastError();
+  }
   const Sched s = make_sched(hl, x.group, NB);
   const size_t lds = 5 * HALF_BYTES;
-  // gathered rows are addressed with 32-bit byte offsets from the head base
-  if ((uint64_t)x.N * (uint64_t)x.k_st * 2u >= (1ull << 32) || (uint64_t)x.N * (uint64_t)x.v_st * 2u >= (1ull << 32))
-    return hipErrorInvalidValue;
-  const bool rows256 = x.k_st == D && x.v_st == D;
   const void *fn = rows256 ? reinterpret_cast<const void *>(vs_kernel<true>)
                            : reinterpret_cast<const void *>(vs_kernel<false>);
   hipError_t e = set_lds(fn, lds);

@@ -595,52 +595,36 @@ __global__ __launch_bounds__(1024) void vs_combine_kernel(int n_chunks, const fl
   }
 }
 
-// Top-k + "sparseformat".  blockIdx.y = 0: verticals from the column sums;
-// blockIdx.y = 1: slashes from the diagonal sums, their runs and the run bitmap.
-__global__ __launch_bounds__(1024) void vs_select_kernel(int N, int nv, int ns, const float *colsum,
-                                                         const float *diagsum, int32_t *v_idx,
-                                                         int32_t *s_idx, int32_t *cover,
-                                                         uint32_t *cover_bits, int32_t *counts,
-                                                         int cover_words) {
-  __shared__ int hist[256];
-  __shared__ int sh[40];
-  const int slot = blockIdx.x, which = blockIdx.y, tid = threadIdx.x;
-  const float *data = (which == 0 ? colsum : diagsum) + (int64_t)slot * N;
-  const int kcap = which == 0 ? nv : ns;
-  const int k = min(kcap, N);
-  int32_t *out = which == 0 ? v_idx + (int64_t)slot * nv : s_idx + (int64_t)slot * ns;
-  unsigned thr;
-  int take_eq;
-  radix_select<1024, true>(data, N, k, &thr, &take_eq, hist, sh);      // N % 64 == 0, rows 256-byte aligned
-  ordered_select<1024, true>(data, N, thr, take_eq, out, sh + 8);
-  for (int i = k + tid; i < kcap; i += 1024) out[i] = 0;
-  if (which == 0) {
-    if (tid == 0) counts[slot * 4 + 0] = k;
-    return;
-  }
-  // ---- slash runs: a gap of more than 64 between neighbouring kept offsets ends a run
-  uint32_t *bits = cover_bits + (int64_t)slot * cover_words;
+// "sparseformat" (Alg. 2; the role of Alg. 4, App. C.4.2): the ascending kept slash offsets
+// offs[0 .. k) of one head become offset runs [t0, t1) -- slash o covers the offsets (o - 64, o],
+// the 64 x 64 tile whose main diagonal it is; neighbours at most 64 apart merge -- and the run
+// bitmap (bit t + 64 set iff offset t is covered).  1024 threads; sh: 16 ints of LDS.  Returns the
+// number of runs.  Offsets are clamped into [0, N), so that a list the caller filled badly cannot
+// make the bitmap writes leave the head's words.
+__device__ inline int vs_merge_runs(const int32_t *offs, int k, int N, int2 *runs, uint32_t *bits,
+                                    int cover_words, int *sh) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   for (int i = tid; i < cover_words; i += 1024) bits[i] = 0u;
   __threadfence_block();
   __syncthreads();
-  int2 *runs = reinterpret_cast<int2 *>(cover) + (int64_t)slot * ns;
+  auto at = [&](int i) { return min(max(offs[i], 0), N - 1); };
   int run_base = 0;
-  const int lane = tid & 63, wave = tid >> 6;
+  // ---- a gap of more than 64 between neighbouring kept offsets ends a run
   for (int i0 = 0; i0 < k; i0 += 1024) {
     const int i = i0 + tid;
     int o = 0;
     bool start = false, last = false;
     if (i < k) {
-      o = out[i];
-      start = i == 0 || o - out[i - 1] > 64;
-      last = i == k - 1 || out[i + 1] - o > 64;
+      o = at(i);
+      start = i == 0 || o - at(i - 1) > 64;
+      last = i == k - 1 || at(i + 1) - o > 64;
     }
     const unsigned long long sb = __builtin_amdgcn_ballot_w64(start);
-    if (lane == 0) sh[8 + wave] = __builtin_popcountll(sb);
+    if (lane == 0) sh[wave] = __builtin_popcountll(sb);
     __syncthreads();
     int before = run_base, total = 0;
     for (int w = 0; w < 16; ++w) {
-      const int c = sh[8 + w];
+      const int c = sh[w];
       if (w < wave) before += c;
       total += c;
     }
@@ -669,9 +653,57 @@ __global__ __launch_bounds__(1024) void vs_select_kernel(int N, int nv, int ns, 
       else bits[w] = m;
     }
   }
+  return run_base;
+}
+
+// Top-k + "sparseformat".  blockIdx.y = 0: verticals from the column sums;
+// blockIdx.y = 1: slashes from the diagonal sums, their runs and the run bitmap.
+__global__ __launch_bounds__(1024) void vs_select_kernel(int N, int nv, int ns, const float *colsum,
+                                                         const float *diagsum, int32_t *v_idx,
+                                                         int32_t *s_idx, int32_t *cover,
+                                                         uint32_t *cover_bits, int32_t *counts,
+                                                         int cover_words) {
+  __shared__ int hist[256];
+  __shared__ int sh[40];
+  const int slot = blockIdx.x, which = blockIdx.y, tid = threadIdx.x;
+  const float *data = (which == 0 ? colsum : diagsum) + (int64_t)slot * N;
+  const int kcap = which == 0 ? nv : ns;
+  const int k = min(kcap, N);
+  int32_t *out = which == 0 ? v_idx + (int64_t)slot * nv : s_idx + (int64_t)slot * ns;
+  unsigned thr;
+  int take_eq;
+  radix_select<1024, true>(data, N, k, &thr, &take_eq, hist, sh);      // N % 64 == 0, rows 256-byte aligned
+  ordered_select<1024, true>(data, N, thr, take_eq, out, sh + 8);
+  for (int i = k + tid; i < kcap; i += 1024) out[i] = 0;
+  if (which == 0) {
+    if (tid == 0) counts[slot * 4 + 0] = k;
+    return;
+  }
+  const int n_runs = vs_merge_runs(out, k, N, reinterpret_cast<int2 *>(cover) + (int64_t)slot * ns,
+                                   cover_bits + (int64_t)slot * cover_words, cover_words, sh + 8);
   if (tid == 0) {
     counts[slot * 4 + 1] = k;
-    counts[slot * 4 + 2] = run_base;
+    counts[slot * 4 + 2] = n_runs;
+    counts[slot * 4 + 3] = 0;
+  }
+}
+
+// "sparseformat" alone, for lines the caller supplies (the static-index use of the attention
+// call): one workgroup per head builds runs, bitmap and the run count from s_idx[0 .. n_s).
+__global__ __launch_bounds__(1024) void vs_lines_kernel(int N, int nv, int ns, const int32_t *s_idx,
+                                                        int32_t *cover, uint32_t *cover_bits,
+                                                        int32_t *counts, int cover_words) {
+  __shared__ int sh[24];
+  const int slot = blockIdx.x;
+  const int n_v = min(max(counts[slot * 4 + 0], 0), nv), n_s = min(max(counts[slot * 4 + 1], 0), ns);
+  __syncthreads();           // every thread has read the counts before thread 0 rewrites them
+  const int n_runs = vs_merge_runs(s_idx + (int64_t)slot * ns, n_s, N,
+                                   reinterpret_cast<int2 *>(cover) + (int64_t)slot * ns,
+                                   cover_bits + (int64_t)slot * cover_words, cover_words, sh);
+  if (threadIdx.x == 0) {
+    counts[slot * 4 + 0] = n_v;
+    counts[slot * 4 + 1] = n_s;
+    counts[slot * 4 + 2] = n_runs;
     counts[slot * 4 + 3] = 0;
   }
 }
@@ -961,6 +993,13 @@ hipError_t launch_build_vs(const QKV &x, const HeadList &hl, int last_q, int nv,
                      (const float *)ml_fin, colsum, diagsum);
   hipLaunchKernelGGL(vs_select_kernel, dim3(hl.n, 2), dim3(1024), 0, st, N, nv, ns, (const float *)colsum,
                      (const float *)diagsum, v_idx, s_idx, cover, cover_bits, counts, cover_words);
+  return hipGetLastError();
+}
+
+hipError_t launch_vs_lines(int N, int rows, int nv, int ns, const int32_t *s_idx, int32_t *cover,
+                           uint32_t *cover_bits, int32_t *counts, int cover_words, hipStream_t st) {
+  hipLaunchKernelGGL(vs_lines_kernel, dim3(rows), dim3(1024), 0, st, N, nv, ns, s_idx, cover, cover_bits, counts,
+                     cover_words);
   return hipGetLastError();
 }
 

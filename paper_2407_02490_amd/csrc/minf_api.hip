@@ -125,6 +125,16 @@ minf_status minf_build_vs_index(const minf_qkv *x, const int32_t *heads, int32_t
   return MINF_OK;
 }
 
+minf_status minf_vs_index_from_lines(int32_t seq_len, int32_t rows, minf_vs_index *idx, void *hip_stream) {
+  if (!idx || !idx->v_idx || !idx->s_idx || !idx->cover || !idx->cover_bits || !idx->counts) return MINF_ERR_NULL;
+  if (seq_len < MINF_BLOCK || seq_len % MINF_BLOCK != 0 || rows < 1) return MINF_ERR_SHAPE;
+  if (idx->block != MINF_BLOCK) return MINF_ERR_UNSUPPORTED;
+  if (idx->nv < 1 || idx->ns < 1) return MINF_ERR_BUDGET;
+  if (idx->cover_words < minf_vs_cover_words(seq_len)) return MINF_ERR_SHAPE;
+  return from_hip(launch_vs_lines(seq_len, rows, idx->nv, idx->ns, idx->s_idx, idx->cover, idx->cover_bits,
+                                  idx->counts, idx->cover_words, static_cast<hipStream_t>(hip_stream)));
+}
+
 minf_status minf_build_bs_index(const minf_qkv *x, const int32_t *heads, int32_t n_heads,
                                 int32_t block, int32_t topk, minf_bs_index *out, void *ws,
                                 size_t ws_bytes, void *hip_stream) {
@@ -183,6 +193,10 @@ minf_status minf_vs_attn(const minf_qkv *x, const int32_t *heads, int32_t n_head
   if (idx->block != MINF_BLOCK) return MINF_ERR_UNSUPPORTED;
   if (idx->nv < 1 || idx->ns < 1) return MINF_ERR_BUDGET;
   if (idx->cover_words < minf_vs_cover_words(x->seq_len)) return MINF_ERR_SHAPE;
+  // the gathered verticals are addressed with 32-bit byte offsets from the head's first row
+  if ((uint64_t)x->seq_len * (uint64_t)x->k_stride[2] * 2u >= (1ull << 32) ||
+      (uint64_t)x->seq_len * (uint64_t)x->v_stride[2] * 2u >= (1ull << 32))
+    return MINF_ERR_SHAPE;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   for (int b = 0; b < x->batch; ++b) {
     const int64_t r = (int64_t)b * n_heads;

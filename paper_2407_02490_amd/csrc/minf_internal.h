@@ -112,6 +112,8 @@ size_t bs_index_ws_bytes(int N, int n_heads);
 hipError_t launch_build_vs(const QKV &x, const HeadList &hl, int last_q, int nv, int ns,
                            int32_t *v_idx, int32_t *s_idx, int32_t *cover, uint32_t *cover_bits,
                            int32_t *counts, int cover_words, void *ws, hipStream_t st);
+hipError_t launch_vs_lines(int N, int rows, int nv, int ns, const int32_t *s_idx, int32_t *cover,
+                           uint32_t *cover_bits, int32_t *counts, int cover_words, hipStream_t st);
 hipError_t launch_build_bs(const QKV &x, const HeadList &hl, int topk, int32_t *blk_idx,
                            int32_t *blk_cnt, int32_t *order, void *ws, hipStream_t st);
 

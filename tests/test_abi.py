@@ -50,24 +50,19 @@ def test_null_arguments_are_rejected_on_the_host(lib):
     assert lib.minf_bs_attn(None, None, 0, None, None) == 1
 
 
-def test_host_run_merge_matches_oracle_cover():
-    """binding.vs_index_from_host merges slash tiles into offset runs on the
-    host; compare with the oracle's offset-space cover (CPU tensors only)."""
-    import torch
-    from oracle import minference_oracle as O
-    from paper_2407_02490_amd import binding as B
-    if not os.path.exists(LIB):
-        pytest.skip("library not built")
-    N = 2048
-    rng = np.random.default_rng(3)
-    S = np.sort(rng.choice(N, 40, replace=False))
-    idx = B.vs_index_from_host([[1, 5]], [S.tolist()], N, device="cpu")
-    n_c = int(idx.counts[0, 2])
-    runs = idx.cover[0, :n_c].numpy()
-    cover = O.slash_cover(S, N, 64)
-    mine = np.zeros_like(cover)
-    for t0, t1 in runs:
-        mine[t0 + 64:t1 + 64] = True
-    assert np.array_equal(mine, cover)
-    bits = np.unpackbits(idx.cover_bits[0].numpy().view(np.uint8), bitorder="little")
-    assert np.array_equal(bits[:N + 64].astype(bool), cover)
+def test_vs_index_from_lines_rejects_bad_arguments_on_the_host(lib):
+    from paper_2407_02490_amd.binding import _VSIndex
+    idx = _VSIndex()
+    assert lib.minf_vs_index_from_lines(1024, 1, None, None) == 1
+    assert lib.minf_vs_index_from_lines(1024, 1, ctypes.byref(idx), None) == 1          # NULL buffers
+    for name in ("v_idx", "s_idx", "cover", "cover_bits", "counts"):
+        setattr(idx, name, 256)                                                         # never dereferenced
+    idx.nv, idx.ns, idx.block, idx.cover_words = 4, 4, 64, 64
+    assert lib.minf_vs_index_from_lines(1000, 1, ctypes.byref(idx), None) == 2          # seq_len % 64
+    assert lib.minf_vs_index_from_lines(1024, 0, ctypes.byref(idx), None) == 2          # no rows
+    idx.cover_words = 3
+    assert lib.minf_vs_index_from_lines(1024, 1, ctypes.byref(idx), None) == 2          # bitmap too small
+    idx.cover_words, idx.block = 64, 32
+    assert lib.minf_vs_index_from_lines(1024, 1, ctypes.byref(idx), None) == 5
+    idx.block, idx.ns = 64, 0
+    assert lib.minf_vs_index_from_lines(1024, 1, ctypes.byref(idx), None) == 3

@@ -227,6 +227,86 @@ def test_vs_matches_oracle(B, N, Vl, Sl):
         assert_close_rows(o[h], want, f"vs N={N} head {h}")
 
 
+@pytest.fixture
+def ring_engine():
+    """Selects the shared-tile Vertical-Slash engine (four waves per workgroup) for one test."""
+    import os
+    old = os.environ.get("MINF_VS_ENGINE")
+    os.environ["MINF_VS_ENGINE"] = "ring"
+    yield
+    if old is None:
+        del os.environ["MINF_VS_ENGINE"]
+    else:
+        os.environ["MINF_VS_ENGINE"] = old
+
+
+RING_CASES = VS_CASES + [
+    # 21 and 13 blocks: the last workgroup has idle waves; narrow, wide and neighbouring runs,
+    # runs that start before key 0 for some of the four blocks of a workgroup only
+    (1344, [0, 7, 640, 1300], [0, 1, 2, 3, 64, 130, 131, 400, 401, 402, 700, 1000, 1343]),
+    (832, list(range(0, 832, 5)), list(range(0, 200)) + [300, 301, 302, 500, 831]),
+    (64, [3], [0]),
+]
+
+
+@pytest.mark.parametrize("N,Vl,Sl", RING_CASES)
+def test_vs_ring_engine_matches_oracle(B, ring_engine, N, Vl, Sl):
+    q, k, v = random_qkv(7, 2, 1, N)
+    dev = B.vs_index_from_host([Vl, Vl], [Sl, Sl], N)
+    o = run_heads(B.minf_vs_attn, q, k, v, [0, 1], dev)
+    for h in (0, 1):
+        want = O.vs_attention(to_f64(q[h]), to_f64(k[0]), to_f64(v[0]), Vl, Sl, Bm=64)
+        assert_close_rows(o[h], want, f"vs ring N={N} head {h}")
+
+
+def test_vs_ring_engine_many_runs_token_major_and_fallback(B, ring_engine, rng):
+    """More than 64 runs (the run list is taken 64 at a time), the general-stride tile fetch, and
+    the exact two-pass fallback, all through the shared-tile engine."""
+    N = 32768
+    q0, k0, v0 = random_qkv(23, 2, 1, N)
+    Sl = sorted(set(rng.choice(N, 150, replace=False).tolist()) | set(range(0, 100)))
+    Vl = sorted(rng.choice(N, 300, replace=False).tolist())
+    dev = B.vs_index_from_host([Vl, Vl], [Sl, Sl], N)
+    assert int(dev.counts[0, 2]) > 64
+    q, k, v = token_major(q0), token_major(k0), token_major(v0)
+    o = token_major(torch.full_like(q0, float("nan")))
+    B.minf_vs_attn(q, k, v, o, [0, 1], dev)
+    torch.cuda.synchronize()
+    blocks = [0, 1, 2, 3, 4, 63, 64, 100, 255, 256, 257, 510, 511]
+    for h in (0, 1):
+        Qh, Kh, Vh = to_f64(q0[h]), to_f64(k0[0]), to_f64(v0[0])
+        for b in blocks:
+            want = O.vs_attention(Qh, Kh, Vh, Vl, Sl, 64 * b, 64 * b + 64, Bm=64)
+            assert_close_rows(o[h, 64 * b:64 * b + 64], want, f"ring token-major head {h} block {b}")
+    k1 = k0.clone()
+    k1[:, 20000:] *= 60.0
+    o = run_heads(B.minf_vs_attn, q0, k1, v0, [0, 1], dev)
+    for b in (300, 400, 511):
+        want = O.vs_attention(to_f64(q0[1]), to_f64(k1[0]), to_f64(v0[0]), Vl, Sl, 64 * b, 64 * b + 64, Bm=64)
+        assert_close_rows(o[1, 64 * b:64 * b + 64], want, f"ring fallback block {b}")
+
+
+def test_scale_other_than_default_through_vs_and_bs(B, rng):
+    """softmax_scale != 1/sqrt(d) through both sparse attention calls (caller-filled indices)."""
+    N, NB, scale = 1024, 16, 0.21
+    q, k, v = random_qkv(31, 2, 1, N)
+    Vl, Sl = [0, 5, 300, 777], [0, 1, 2, 200, 201, 640]
+    dev = B.vs_index_from_host([Vl, Vl], [Sl, Sl], N)
+    o = torch.full_like(q, float("nan"))
+    B.minf_vs_attn(q, k, v, o, [0, 1], dev, scale=scale)
+    idxs = [random_bs_index(rng, NB, 4) for _ in range(2)]
+    devb = B.bs_index_from_host(np.stack([i for i, _ in idxs]), np.stack([c for _, c in idxs]))
+    ob = torch.full_like(q, float("nan"))
+    B.minf_bs_attn(q, k, v, ob, [0, 1], devb, scale=scale)
+    torch.cuda.synchronize()
+    for h in (0, 1):
+        Qh, Kh, Vh = to_f64(q[h]), to_f64(k[0]), to_f64(v[0])
+        assert_close_rows(o[h], O.vs_attention(Qh, Kh, Vh, Vl, Sl, Bm=64, scale=scale), f"vs scale head {h}")
+        assert_close_rows(ob[h], O.bs_attention(Qh, Kh, Vh, idxs[h][0], idxs[h][1], scale=scale), f"bs scale head {h}")
+        # the scale matters: the default-scale result is far outside the bar
+        assert np.abs(O.vs_attention(Qh, Kh, Vh, Vl, Sl, Bm=64) - o[h].double().cpu().numpy()).max() > 5e-2
+
+
 def test_vs_many_columns_more_than_one_round(B, rng):
     # more kept verticals than one LDS round holds (1024): the column phase runs twice
     N = 2048

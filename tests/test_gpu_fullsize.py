@@ -4,8 +4,12 @@ times: the 128K single-pattern layers (c1, c2, c3) and the mixed 1M layer (c4).
 The oracle cannot do a whole layer in fp64 in reasonable time, so outputs are
 checked on sampled 64-row query blocks (rows are independent given the
 indices): block 0, the last block, the blocks that straddle the A-shape sink
-and window edges, the first block with a full Block-Sparse budget, plus seeded
-random blocks.  Index sets are checked in full for the sampled heads.
+and window edges, the first block with a full Block-Sparse budget, plus at least twelve
+seeded random blocks per sampled head; three heads per pattern from different
+K/V groups.  Index sets are checked in full for the sampled heads (at 1M
+tokens every Block-Sparse index row of one head, sampled rows of the others).
+Next to the absolute bar every block must be close in relative L2 norm
+(tests/helpers.py), which a dropped tile or a dropped gathered step fails.
 """
 import numpy as np
 import pytest
@@ -13,7 +17,7 @@ import torch
 
 from oracle import minference_oracle as O
 from paper_2407_02490_amd import workloads as W
-from tests.helpers import assert_close_rows, check_topk
+from tests.helpers import assert_close_rows, check_topk, observed_errors
 
 pytestmark = pytest.mark.gpu
 
@@ -58,19 +62,19 @@ def test_c2_vertical_slash_128k(B):
     B.minf_vs_attn(x.q, x.k, x.v, o, heads, idx)
     torch.cuda.synchronize()
     NB = N // 64
-    blocks = sample_blocks(NB, [1, 2, 100], 8, 2)
     swaps = 0
-    for h in (0, 17, 30):
+    for n, h in enumerate((0, 17, 30)):                         # three K/V groups
+        blocks = sample_blocks(NB, [1, 2, 100, NB - 2], 12, 20 + n)
         Qh, Kh, Vh = x.head_f64(h)
         Vo, So, col, diag = O.vs_index(Qh, Kh, c["last_q"], c["nv"], c["ns"])
         Vg = idx.v_idx[h].cpu().numpy()
         Sg = idx.s_idx[h].cpu().numpy()
-        swaps += check_topk(Vg, col, c["nv"]) + check_topk(Sg, diag, c["ns"])
+        swaps += check_topk(Vg, col, c["nv"], max_swaps=4) + check_topk(Sg, diag, c["ns"], max_swaps=4)
         assert np.isin(x.sinks[h // 4].numpy(), Vg).mean() >= 0.9      # planted sinks are found
         for b in blocks:
             want = O.vs_attention(Qh, Kh, Vh, Vg, Sg, 64 * b, 64 * b + 64)
             assert_close_rows(o[h, 64 * b:64 * b + 64], want, f"c2 head {h} block {b}")
-    print("c2 tolerated index swaps:", swaps)
+    print("c2 tolerated index swaps:", swaps, "observed errors:", observed_errors())
 
 
 def bs_row_check(idx_row, cnt, Qp, Kp, b, topk, tau):
@@ -90,18 +94,21 @@ def test_c3_block_sparse_128k(B):
     B.minf_bs_attn(x.q, x.k, x.v, o, heads, idx)
     torch.cuda.synchronize()
     NB = N // 64
-    blocks = sample_blocks(NB, [98, 99, 100, 101], 8, 3)
-    for h in (0, 21):
+    for n, h in enumerate((0, 13, 21)):                         # three K/V groups
+        blocks = sample_blocks(NB, [98, 99, 100, 101], 12, 30 + n)
         Qh, Kh, Vh = x.head_f64(h)
         io, co, s = O.bs_index(Qh, Kh, 64, c["topk"])
         got = idx.blk_idx[h].cpu().numpy()
         cnt = idx.blk_cnt[h].cpu().numpy()
         assert np.array_equal(cnt, co)
-        swaps = sum(check_topk(got[b, :cnt[b]], s[b, :b + 1], c["topk"], relative=False) for b in range(NB))
+        # every row of the index
+        swaps = sum(check_topk(got[b, :cnt[b]], s[b, :b + 1], c["topk"], relative=False, max_swaps=2) for b in range(NB))
+        assert swaps <= 8
         print(f"c3 head {h} tolerated index swaps:", swaps)
         for b in blocks:
             want = O.bs_attention(Qh, Kh, Vh, got, cnt, 64 * b, 64 * b + 64)
             assert_close_rows(o[h, 64 * b:64 * b + 64], want, f"c3 head {h} block {b}")
+    print("c3 observed errors:", observed_errors())
 
 
 def test_c4_mixed_1m(B):
@@ -122,29 +129,61 @@ def test_c4_mixed_1m(B):
     assert not torch.isnan(o[:, -1].float()).any()            # every head was written by some call
     NB = N // 64
     tau = 1.0 / np.sqrt(128.0)
-    # one head per pattern
-    r, h = 5, vs_h[5]
-    Qh, Kh, Vh = x.head_f64(h)
-    Vo, So, col, diag = O.vs_index(Qh, Kh, c["last_q"], c["nv"], c["ns"])
-    Vg, Sg = vsi.v_idx[r].cpu().numpy(), vsi.s_idx[r].cpu().numpy()
-    print("c4 VS tolerated index swaps:", check_topk(Vg, col, c["nv"]) + check_topk(Sg, diag, c["ns"]))
-    for b in sample_blocks(NB, [3], 3, 4):
-        want = O.vs_attention(Qh, Kh, Vh, Vg, Sg, 64 * b, 64 * b + 64)
-        assert_close_rows(o[h, 64 * b:64 * b + 64], want, f"c4 VS head {h} block {b}")
-    r, h = 2, bs_h[2]
-    Qh, Kh, Vh = x.head_f64(h)
-    Qp, Kp = O.bs_pool(Qh), O.bs_pool(Kh)
-    got, cnt = bsi.blk_idx[r].cpu().numpy(), bsi.blk_cnt[r].cpu().numpy()
-    assert np.array_equal(cnt, np.minimum(c["topk"], np.arange(1, NB + 1)))
-    for b in sample_blocks(NB, [99, 100], 4, 5):
-        bs_row_check(got[b], cnt[b], Qp, Kp, b, c["topk"], tau)
-        want = O.bs_attention(Qh, Kh, Vh, got, cnt, 64 * b, 64 * b + 64)
-        assert_close_rows(o[h, 64 * b:64 * b + 64], want, f"c4 BS head {h} block {b}")
-    h = a_h[0]
-    Qh, Kh, Vh = x.head_f64(h)
-    for b in sample_blocks(NB, [16, 64, 80], 4, 6):
-        want = O.ashape_attention(Qh, Kh, Vh, c["n_init"], c["n_local"], 64 * b, 64 * b + 64)
-        assert_close_rows(o[h, 64 * b:64 * b + 64], want, f"c4 A-shape head {h} block {b}")
+    g = x.n_q_heads // x.n_kv_heads
+
+    def pick(heads, n):
+        """n positions of a head list whose heads read different K/V heads (as far as there are)."""
+        out, seen = [], set()
+        for r, h in enumerate(heads):
+            if h // g not in seen:
+                seen.add(h // g)
+                out.append(r)
+        out += [r for r in range(len(heads)) if r not in out]
+        return out[:n]
+
+    # Vertical-Slash: three heads of different K/V groups; edge blocks + 12 random ones each
+    swaps = 0
+    for n, r in enumerate(pick(vs_h, 3)):
+        h = vs_h[r]
+        Qh, Kh, Vh = x.head_f64(h)
+        Vo, So, col, diag = O.vs_index(Qh, Kh, c["last_q"], c["nv"], c["ns"])
+        Vg, Sg = vsi.v_idx[r].cpu().numpy(), vsi.s_idx[r].cpu().numpy()
+        swaps += check_topk(Vg, col, c["nv"], max_swaps=4) + check_topk(Sg, diag, c["ns"], max_swaps=4)
+        for b in sample_blocks(NB, [1, 3, NB - 2], 12, 40 + n):
+            want = O.vs_attention(Qh, Kh, Vh, Vg, Sg, 64 * b, 64 * b + 64)
+            assert_close_rows(o[h, 64 * b:64 * b + 64], want, f"c4 VS head {h} block {b}")
+        del Qh, Kh, Vh
+    print("c4 VS tolerated index swaps:", swaps)
+    # Block-Sparse: three heads; every row of the index for the first of them
+    for n, r in enumerate(pick(bs_h, 3)):
+        h = bs_h[r]
+        Qh, Kh, Vh = x.head_f64(h)
+        Qp, Kp = O.bs_pool(Qh), O.bs_pool(Kh)
+        got, cnt = bsi.blk_idx[r].cpu().numpy(), bsi.blk_cnt[r].cpu().numpy()
+        assert np.array_equal(cnt, np.minimum(c["topk"], np.arange(1, NB + 1)))
+        blocks = sample_blocks(NB, [98, 99, 100, 101], 12, 50 + n)
+        rows = range(NB) if n == 0 else blocks
+        bs_swaps = 0
+        for b0 in range(0, NB, 2048):                          # block logits of 2048 rows at a time
+            sc = (Qp[b0:b0 + 2048] @ Kp.T) * tau               # Alg. 3: block logits
+            for b in rows:
+                if b0 <= b < b0 + 2048:
+                    assert cnt[b] == min(c["topk"], b + 1)
+                    bs_swaps += check_topk(got[b, :cnt[b]], sc[b - b0, :b + 1], c["topk"], relative=False, max_swaps=2)
+        print(f"c4 BS head {h}: {len(rows)} index rows checked, tolerated swaps {bs_swaps}")
+        assert bs_swaps <= 16
+        for b in blocks:
+            want = O.bs_attention(Qh, Kh, Vh, got, cnt, 64 * b, 64 * b + 64)
+            assert_close_rows(o[h, 64 * b:64 * b + 64], want, f"c4 BS head {h} block {b}")
+        del Qh, Kh, Vh
+    # A-shape: both heads
+    for n, h in enumerate(a_h):
+        Qh, Kh, Vh = x.head_f64(h)
+        for b in sample_blocks(NB, [15, 16, 17, 63, 64, 65, 79, 80, 81], 12, 60 + n):
+            want = O.ashape_attention(Qh, Kh, Vh, c["n_init"], c["n_local"], 64 * b, 64 * b + 64)
+            assert_close_rows(o[h, 64 * b:64 * b + 64], want, f"c4 A-shape head {h} block {b}")
+        del Qh, Kh, Vh
+    print("c4 observed errors:", observed_errors())
 
 
 def test_ragged_medium_length_mixed(B):
@@ -220,7 +259,7 @@ def test_two_million_tokens_one_head(B):
     Qh, Kh, Vh = x.head_f64(0)
     Vo, So, col, diag = O.vs_index(Qh, Kh, 64, nv, ns)
     Vg, Sg = vsi.v_idx[0].cpu().numpy(), vsi.s_idx[0].cpu().numpy()
-    print("2M VS tolerated index swaps:", check_topk(Vg, col, nv) + check_topk(Sg, diag, ns))
+    print("2M VS tolerated index swaps:", check_topk(Vg, col, nv, max_swaps=4) + check_topk(Sg, diag, ns, max_swaps=4))
     for b in blocks:
         want = O.vs_attention(Qh, Kh, Vh, Vg, Sg, 64 * b, 64 * b + 64)
         assert_close_rows(o[0, 64 * b:64 * b + 64], want, f"2M VS block {b}")

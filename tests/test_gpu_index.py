@@ -66,6 +66,106 @@ def test_vs_index_random_inputs(B, N, last_q, nv, ns):
         check_vs_index(idx, r, N, to_f64(q[h]), to_f64(k[h // 2]), last_q, nv, ns)
 
 
+@pytest.mark.parametrize("N,n_s", [(2048, 40), (4096, 1), (131072, 3000), (1024, 1024)])
+def test_vs_index_from_lines_matches_oracle_cover(B, rng, N, n_s):
+    """Runs, bitmap and counts built on the device from caller-supplied lines (the static-index
+    use) equal the oracle's offset-space cover of the same slashes, bit for bit."""
+    lists = [np.sort(rng.choice(N, n_s, replace=False)), np.sort(rng.choice(N, max(1, n_s // 2), replace=False))]
+    if n_s >= 40:
+        lists[1][:20] = np.arange(20)                       # a contiguous stretch: one wide run
+        lists[1] = np.unique(lists[1])
+    Vl = [[1, 5], list(range(0, N, 97))]
+    idx = B.vs_index_from_host(Vl, [l.tolist() for l in lists], N)
+    torch.cuda.synchronize()
+    for r, S in enumerate(lists):
+        n_v, n_sg, n_c, zero = idx.counts[r].cpu().tolist()
+        assert (n_v, n_sg, zero) == (len(Vl[r]), S.size, 0)
+        assert np.array_equal(idx.s_idx[r, :S.size].cpu().numpy(), S)
+        cover = O.slash_cover(S, N, 64)
+        edges = np.diff(np.concatenate([[0], cover.astype(np.int8), [0]]))
+        t0, t1 = np.flatnonzero(edges == 1) - 64, np.flatnonzero(edges == -1) - 64
+        runs = idx.cover[r, :n_c].cpu().numpy()
+        assert n_c == t0.size and np.array_equal(runs[:, 0], t0) and np.array_equal(runs[:, 1], t1)
+        flat = np.unpackbits(idx.cover_bits[r].cpu().numpy().view(np.uint8), bitorder="little")
+        assert np.array_equal(flat[:N + 64].astype(bool), cover) and not flat[N + 64:].any()
+
+
+def test_vs_index_from_lines_clamps_offsets_outside_the_sequence(B):
+    N = 1024
+    idx = B.vs_index_from_host([[0]], [[5, 700, N + 4000]], N)       # the last offset is not a valid line
+    torch.cuda.synchronize()
+    n_c = int(idx.counts[0, 2])
+    runs = idx.cover[0, :n_c].cpu().numpy()
+    assert runs.min() >= -63 and runs.max() <= N
+    flat = np.unpackbits(idx.cover_bits[0].cpu().numpy().view(np.uint8), bitorder="little")
+    assert np.array_equal(flat[:N + 64].astype(bool), O.slash_cover(np.array([5, 700, N - 1]), N, 64))
+
+
+def test_vs_attn_refuses_rows_too_far_apart_for_the_gather(B):
+    """seq_len * row pitch >= 2^32 bytes: refused with a shape status before any launch."""
+    N = 128
+    q, k, v = random_qkv(15, 1, 1, N)
+    big = torch.empty(1 << 31, dtype=torch.bfloat16, device="cuda")   # 4 GiB, never read
+    kk = torch.as_strided(big, (1, N, 128), (0, 1 << 24, 1))          # the largest row pitch accepted: 32 MiB
+    idx = B.vs_index_from_host([[0]], [[0]], N)
+    o = torch.zeros_like(q)
+    with pytest.raises(B.MinfError) as e:
+        B.minf_vs_attn(q, kk, v, o, [0], idx)
+    assert e.value.status == 2
+    torch.cuda.synchronize()
+    assert (o == 0).all()
+
+
+def test_last_q_17_index_then_attention(B):
+    """Fewer estimating rows than a block (last_q = 17), then attention with that index."""
+    N, nv, ns = 2112, 60, 150
+    q, k, v = random_qkv(13, 2, 1, N)
+    idx = build_vs(B, q, k, [1, 0], 17, nv, ns)
+    o = torch.full_like(q, float("nan"))
+    B.minf_vs_attn(q, k, v, o, [1, 0], idx)
+    torch.cuda.synchronize()
+    for r, h in enumerate([1, 0]):
+        Qh, Kh, Vh = to_f64(q[h]), to_f64(k[0]), to_f64(v[0])
+        Vg, Sg, swaps = check_vs_index(idx, r, N, Qh, Kh, 17, nv, ns)
+        assert swaps == 0
+        assert_close_rows(o[h], O.vs_attention(Qh, Kh, Vh, Vg, Sg, Bm=64), f"last_q=17 head {h}")
+
+
+def test_scale_other_than_default_through_both_builders(B):
+    """softmax_scale != 1/sqrt(d) through minf_build_vs_index / minf_build_bs_index and on into
+    attention: the estimate's softmax sharpens with the scale, so the kept lines change."""
+    N, scale = 2048, 0.2
+    q, k, v = random_qkv(14, 2, 1, N)
+    heads = [0, 1]
+    idx = B.alloc_vs_index(2, 40, 90, N)
+    ws = torch.empty(B.minf_vs_index_workspace_bytes(q, k, 2, 64), dtype=torch.uint8, device="cuda")
+    B.minf_build_vs_index(q, k, heads, 64, 40, 90, idx, ws, scale=scale)
+    bidx = B.alloc_bs_index(2, N, 6)
+    ws2 = torch.empty(B.minf_bs_index_workspace_bytes(q, k, 2), dtype=torch.uint8, device="cuda")
+    B.minf_build_bs_index(q, k, heads, 6, bidx, ws2, scale=scale)
+    o = torch.full_like(q, float("nan"))
+    ob = torch.full_like(q, float("nan"))
+    B.minf_vs_attn(q, k, v, o, heads, idx, scale=scale)
+    B.minf_bs_attn(q, k, v, ob, heads, bidx, scale=scale)
+    torch.cuda.synchronize()
+    changed = 0
+    for r, h in enumerate(heads):
+        Qh, Kh, Vh = to_f64(q[h]), to_f64(k[0]), to_f64(v[0])
+        Vo, So, col, diag = O.vs_index(Qh, Kh, 64, 40, 90, scale=scale)
+        Vg, Sg = idx.v_idx[r].cpu().numpy(), idx.s_idx[r].cpu().numpy()
+        assert check_topk(Vg, col, 40) + check_topk(Sg, diag, 90) == 0
+        Vd, Sd, _, _ = O.vs_index(Qh, Kh, 64, 40, 90)
+        changed += int(not np.array_equal(Vd, Vo)) + int(not np.array_equal(Sd, So))
+        assert_close_rows(o[h], O.vs_attention(Qh, Kh, Vh, Vg, Sg, Bm=64, scale=scale), f"vs scale head {h}")
+        io, co, s = O.bs_index(Qh, Kh, 64, 6, scale=scale)
+        got, cnt = bidx.blk_idx[r].cpu().numpy(), bidx.blk_cnt[r].cpu().numpy()
+        assert np.array_equal(cnt, co)
+        for b in range(N // 64):
+            assert check_topk(got[b, :cnt[b]], s[b, :b + 1], 6, relative=False) == 0
+        assert_close_rows(ob[h], O.bs_attention(Qh, Kh, Vh, got, cnt, scale=scale), f"bs scale head {h}")
+    assert changed > 0          # the case can tell the scales apart
+
+
 def test_vs_index_is_bit_reproducible(B):
     q, k, v = random_qkv(12, 2, 1, 2048)
     a = build_vs(B, q, k, [0, 1], 64, 100, 200)

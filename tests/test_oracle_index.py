@@ -29,15 +29,16 @@ def test_topk_random_against_python_sort(rng):
 
 
 # --------------------------------------------------- Alg. 2: VS estimate
-def brute_vs_scores(Q, K, last_q):
+def brute_vs_scores(Q, K, last_q, tau=None):
     """Explicit loops over (r, j): softmax rows of the last queries, column
     sums and diagonal sums."""
     N, d = K.shape
     R = min(last_q, N)
+    tau = 1.0 / math.sqrt(d) if tau is None else tau
     A = np.zeros((R, N))
     for r in range(R):
         p = N - R + r
-        logits = [sum(Q[p, c] * K[j, c] for c in range(d)) / math.sqrt(d) for j in range(p + 1)]
+        logits = [sum(Q[p, c] * K[j, c] for c in range(d)) * tau for j in range(p + 1)]
         mx = max(logits)
         e = [math.exp(x - mx) for x in logits]
         z = sum(e)
@@ -68,6 +69,22 @@ def test_vs_scores_bruteforce(rng, N, last_q):
     wantV = sorted(sorted(range(N), key=lambda j: (-col[j], j))[:min(nv, N)])
     wantS = sorted(sorted(range(N), key=lambda o: (-diag[o], o))[:min(ns, N)])
     assert list(V) == wantV and list(S) == wantS
+
+
+def test_vs_scores_bruteforce_with_a_scale_other_than_the_default(rng):
+    """The scale argument multiplies the logits before the softmax (Eq. 1's 1/sqrt(d) replaced):
+    a sharper softmax changes the line scores and the kept lines."""
+    N, d, last_q, tau = 40, 8, 6, 0.9
+    Q, K = rng.normal(size=(2, N, d))
+    A, col, diag = brute_vs_scores(Q, K, last_q, tau)
+    A2 = O.vs_estimate(Q, K, last_q, scale=tau)
+    col2, diag2 = O.vs_line_scores(A2)
+    assert np.allclose(A, A2, atol=1e-14) and np.allclose(col, col2, atol=1e-14) and np.allclose(diag, diag2, atol=1e-14)
+    assert not np.allclose(A2, O.vs_estimate(Q, K, last_q), atol=1e-3)        # the argument is not ignored
+    V, S, c3, d3 = O.vs_index(Q, K, last_q, 4, 6, scale=tau)
+    assert np.allclose(c3, col, atol=1e-14) and np.allclose(d3, diag, atol=1e-14)
+    assert list(V) == sorted(sorted(range(N), key=lambda j: (-col[j], j))[:4])
+    assert list(S) == sorted(sorted(range(N), key=lambda o: (-diag[o], o))[:6])
 
 
 def test_vs_scores_mass_invariant(rng):
@@ -253,6 +270,43 @@ def test_bs_index_bruteforce(rng):
         assert cnt[b] == min(k, b + 1)
         assert list(idx[b, :cnt[b]]) == want[b]
         assert np.all(idx[b, cnt[b]:] == -1)
+
+
+def test_bs_scores_with_a_scale_other_than_the_default(rng):
+    """Block logits are tau * <Q_hat_b, K_hat_c>: explicit loops with tau = 0.37."""
+    N, d, B, tau = 96, 6, 8, 0.37
+    Q, K = rng.normal(size=(2, N, d))
+    NB = N // B
+    s = O.bs_scores(Q, K, B, scale=tau)
+    for b in range(NB):
+        for c in range(NB):
+            if c > b:
+                assert s[b, c] == -np.inf
+                continue
+            qb = [sum(Q[b * B + t, x] for t in range(B)) / B for x in range(d)]
+            kc = [sum(K[c * B + t, x] for t in range(B)) / B for x in range(d)]
+            assert abs(s[b, c] - tau * sum(qb[x] * kc[x] for x in range(d))) < 1e-13
+    idx, cnt, s2 = O.bs_index(Q, K, B, 3, scale=tau)
+    assert np.array_equal(s, s2)
+    # a positive scale does not change the selection (Alg. 3 keeps the largest logits per row)
+    idx0, cnt0, _ = O.bs_index(Q, K, B, 3)
+    assert np.array_equal(idx, idx0) and np.array_equal(cnt, cnt0)
+
+
+def test_bs_tile_count_is_the_number_of_tiles_the_mask_touches(rng):
+    """tiles_bs against the explicit mask: per query block, the number of B x B tiles of the
+    Block-Sparse mask that hold a permitted (query, key) pair."""
+    N, B, k = 160, 8, 4
+    NB = N // B
+    idx = -np.ones((NB, k), dtype=np.int64)
+    cnt = np.zeros(NB, dtype=np.int64)
+    for b in range(NB):
+        c = int(rng.integers(1, min(k, b + 1) + 1))
+        idx[b, :c] = np.sort(rng.choice(b + 1, c, replace=False))
+        cnt[b] = c
+    M = O.bs_rows(0, N, N, idx, cnt, B)
+    touched = M.reshape(NB, B, NB, B).any(axis=(1, 3)).sum(axis=1)
+    assert np.array_equal(O.tiles_bs(cnt), touched)
 
 
 def test_bs_selection_on_logits_equals_selection_on_softmax(rng):
