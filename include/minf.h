@@ -138,6 +138,28 @@ minf_status minf_build_vs_index(const minf_qkv *x, const int32_t *heads, int32_t
                                 void *hip_stream);
 
 /*
+ * minf_build_vs_index for callers that cannot allocate device memory and have
+ * no workspace to pass: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, checks and results as
+ * minf_build_vs_index, but the line scores and softmax statistics go to a
+ * scratch array that is part of the library (a file-scope device array of
+ * MINF_NOALLOC_SCRATCH_BYTES bytes per GPU, held until the process ends)
+ * instead of `ws`.  Allocates nothing, frees nothing, synchronises nothing.
+ * Inputs whose workspace need (minf_vs_index_workspace_bytes) exceeds
+ * MINF_NOALLOC_SCRATCH_BYTES are refused with MINF_ERR_WORKSPACE; with
+ * batch > 1 the batch elements use the array one after the other on the
+ * stream.  All calls on one GPU share that GPU's array: calls that overlap
+ * in time on one GPU (different streams, different threads) race; nothing in
+ * the array needs clearing between calls (every word that is read was
+ * written by the same call).  The array's device address is looked up on the
+ * first call on each device (MINF_ERR_HIP if the runtime refuses).
+ */
+#define MINF_NOALLOC_SCRATCH_BYTES (64u << 20)
+minf_status minf_build_vs_index_noalloc(const minf_qkv *x, const int32_t *heads, int32_t n_heads,
+                                        int32_t last_q, int32_t nv, int32_t ns, int32_t block,
+                                        minf_vs_index *out, void *hip_stream);
+
+/*
  * The "sparseformat" step alone (Alg. 2; Alg. 4's role, App. C.4.2) for lines
  * the caller chose: the static-index use of the attention call (Section 4,
  * ablation "Ours w/ static").  On entry, for every row r < rows of idx:

@@ -13,7 +13,7 @@ import torch
 __all__ = [
     "lib", "MinfError", "VSIndex", "BSIndex", "alloc_vs_index", "alloc_bs_index",
     "vs_index_from_host", "bs_index_from_host",
-    "minf_build_vs_index", "minf_vs_index_from_lines", "minf_build_bs_index", "minf_ashape_attn", "minf_vs_attn",
+    "minf_build_vs_index", "minf_build_vs_index_noalloc", "minf_vs_index_from_lines", "minf_build_bs_index", "minf_ashape_attn", "minf_vs_attn",
     "minf_bs_attn", "minf_dense_attn", "minf_vs_cover_words",
     "minf_vs_index_workspace_bytes", "minf_bs_index_workspace_bytes",
 ]
@@ -73,6 +73,8 @@ def lib():
     L.minf_bs_index_workspace_bytes.argtypes = [pq, i32]
     L.minf_build_vs_index.restype = ctypes.c_int
     L.minf_build_vs_index.argtypes = [pq, pi, i32, i32, i32, i32, i32, ctypes.POINTER(_VSIndex), vp, sz, vp]
+    L.minf_build_vs_index_noalloc.restype = ctypes.c_int
+    L.minf_build_vs_index_noalloc.argtypes = [pq, pi, i32, i32, i32, i32, i32, ctypes.POINTER(_VSIndex), vp]
     L.minf_vs_index_from_lines.restype = ctypes.c_int
     L.minf_vs_index_from_lines.argtypes = [i32, i32, ctypes.POINTER(_VSIndex), vp]
     L.minf_build_bs_index.restype = ctypes.c_int
@@ -238,6 +240,14 @@ def minf_build_vs_index(q, k, heads, last_q, nv, ns, out, ws, block=BLOCK, scale
     _check(lib().minf_build_vs_index(ctypes.byref(x), h, n, last_q, nv, ns, block, ctypes.byref(s),
                                      ctypes.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size(),
                                      _stream(stream)))
+
+
+def minf_build_vs_index_noalloc(q, k, heads, last_q, nv, ns, out, block=BLOCK, scale=0.0, stream=None):
+    x = _qkv(q, k, scale=scale)
+    h, n = _heads(heads)
+    s = out.c_struct()
+    _check(lib().minf_build_vs_index_noalloc(ctypes.byref(x), h, n, last_q, nv, ns, block, ctypes.byref(s),
+                                             _stream(stream)))
 
 
 def minf_vs_index_from_lines(idx, stream=None):

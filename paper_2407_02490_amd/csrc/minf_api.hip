@@ -4,11 +4,39 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "minf_internal.h"
 
 using namespace minf;
 
+// Scratch memory of minf_build_vs_index_noalloc: line scores and partial softmax statistics of
+// the Vertical-Slash index build.  One copy per GPU, held until the process ends.  In host code
+// the array's name is only a handle for hipGetSymbolAddress; the device address it yields (one
+// per device) is what the kernels receive.  (No `used` attribute: the compiler gives a static
+// device variable that host code names a visible symbol in the code object, which the runtime's
+// lookup needs, only without it.)
+static __device__ __align__(256) unsigned char scratch[MINF_NOALLOC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+void *g_scratch_ptr[MAX_DEVICES];          // device address of `scratch` on each device, once looked up
+std::mutex g_scratch_mutex;
+
+// Device address of the scratch array on the current device (looked up on the first call on
+// that device, with that device current).  nullptr if the runtime refuses.
+void *scratch_on_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
 
 minf_status check_qkv(const minf_qkv *x, bool need_v_o) {
   if (!x || !x->q || !x->k) return MINF_ERR_NULL;
@@ -97,9 +125,9 @@ size_t minf_bs_index_workspace_bytes(const minf_qkv *x, int32_t n_heads) {
   return bs_index_ws_bytes(x->seq_len, n_heads);
 }
 
-minf_status minf_build_vs_index(const minf_qkv *x, const int32_t *heads, int32_t n_heads,
-                                int32_t last_q, int32_t nv, int32_t ns, int32_t block,
-                                minf_vs_index *out, void *ws, size_t ws_bytes, void *hip_stream) {
+static minf_status build_vs_common(const minf_qkv *x, const int32_t *heads, int32_t n_heads, int32_t last_q,
+                                   int32_t nv, int32_t ns, int32_t block, minf_vs_index *out, void *ws,
+                                   size_t ws_bytes, bool own_scratch, void *hip_stream) {
   minf_status s = check_qkv(x, false);
   if (s != MINF_OK) return s;
   HeadList hl;
@@ -111,8 +139,14 @@ minf_status minf_build_vs_index(const minf_qkv *x, const int32_t *heads, int32_t
   if (out->nv != nv || out->ns != ns || out->block != block) return MINF_ERR_BUDGET;
   if (out->cover_words < minf_vs_cover_words(x->seq_len)) return MINF_ERR_SHAPE;
   const size_t need = vs_index_ws_bytes(x->seq_len, n_heads);
-  if (!ws || ws_bytes < need) return MINF_ERR_WORKSPACE;
-  if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return MINF_ERR_WORKSPACE;
+  if (own_scratch) {
+    if (need > (size_t)MINF_NOALLOC_SCRATCH_BYTES) return MINF_ERR_WORKSPACE;
+    ws = scratch_on_current_device();
+    if (!ws) return MINF_ERR_HIP;
+  } else {
+    if (!ws || ws_bytes < need) return MINF_ERR_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return MINF_ERR_WORKSPACE;
+  }
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   for (int b = 0; b < x->batch; ++b) {
     const int64_t r = (int64_t)b * n_heads;
@@ -123,6 +157,18 @@ minf_status minf_build_vs_index(const minf_qkv *x, const int32_t *heads, int32_t
     if (e != hipSuccess) return MINF_ERR_HIP;
   }
   return MINF_OK;
+}
+
+minf_status minf_build_vs_index(const minf_qkv *x, const int32_t *heads, int32_t n_heads,
+                                int32_t last_q, int32_t nv, int32_t ns, int32_t block,
+                                minf_vs_index *out, void *ws, size_t ws_bytes, void *hip_stream) {
+  return build_vs_common(x, heads, n_heads, last_q, nv, ns, block, out, ws, ws_bytes, false, hip_stream);
+}
+
+minf_status minf_build_vs_index_noalloc(const minf_qkv *x, const int32_t *heads, int32_t n_heads,
+                                        int32_t last_q, int32_t nv, int32_t ns, int32_t block,
+                                        minf_vs_index *out, void *hip_stream) {
+  return build_vs_common(x, heads, n_heads, last_q, nv, ns, block, out, nullptr, 0, true, hip_stream);
 }
 
 minf_status minf_vs_index_from_lines(int32_t seq_len, int32_t rows, minf_vs_index *idx, void *hip_stream) {
