@@ -137,6 +137,16 @@ class Layer:
             out["bs_attn"] = int(C.bs_index_tiles(self.bs_idx).sum())
         return out
 
+    def executed_tiles(self):
+        """Work the attention kernels execute, in 64 x 64 tile units (what the FLOP rate is computed
+        from).  Vertical-Slash: 64 x 32 steps / 2 (a run is walked 32 keys at a time, so a run whose
+        length mod 64 is in 1 .. 32 costs half a tile less than the canonical count).  A-shape and
+        Block-Sparse: the canonical tiles (the kernels run whole 64-key tiles / block pairs of steps)."""
+        out = self.tiles()
+        if self.vs_heads:
+            out["vs_attn"] = int(C.vs_index_steps(self.vs_idx, self.N).sum()) / 2.0
+        return out
+
     def nnz(self):
         """Permitted (query, key) pairs per attention call: the useful work, 4 * d FLOP each."""
         out = {}
@@ -150,9 +160,10 @@ class Layer:
 
     def report(self, wall_ms):
         tiles = self.tiles()
+        done = self.executed_tiles()
         nnz = self.nnz()
         r = {"workload": self.name, "seq_len": self.N, "ms_per_layer": round(wall_ms, 4), "calls": {}}
-        tot_tiles = 0
+        tot_tiles = tot_done = 0
         for k, t in self.t.items():
             ms = t.ms()
             if not ms:
@@ -170,16 +181,22 @@ class Layer:
                 by = (len(self.bs_heads) + kv) * self.N * 256
                 e.update({"algorithmic_bytes": by, "gb_per_s": round(by / (e["ms"] * 1e-3) / 1e9, 1)})
             if k in tiles:
+                # tiles: canonical 64 x 64 decomposition of the mask (the cost model's unit);
+                # executed_tiles: what the kernel computes (VS: 32-key steps); the rate uses the latter
                 e["tiles"] = tiles[k]
-                e["tflops"] = round(tiles[k] * FT / (e["ms"] * 1e-3) / 1e12, 2)
+                e["executed_tiles"] = done[k]
+                e["tflops"] = round(done[k] * FT / (e["ms"] * 1e-3) / 1e12, 2)
                 e["frac_of_bf16_peak"] = round(e["tflops"] / PEAK_BF16_TFLOPS, 4)
+                e["tflops_of_canonical_tiles"] = round(tiles[k] * FT / (e["ms"] * 1e-3) / 1e12, 2)
                 # FLOPs of the permitted pairs only (a tile also pays for its masked part)
                 e["useful_tflops"] = round(4 * 128 * nnz[k] / (e["ms"] * 1e-3) / 1e12, 2)
                 e["mask_fill_of_tiles"] = round(nnz[k] / (tiles[k] * 64 * 64), 4)
                 tot_tiles += tiles[k]
+                tot_done += done[k]
             r["calls"][k] = e
         r["tiles"] = tot_tiles
-        r["effective_tflops"] = round(tot_tiles * FT / (wall_ms * 1e-3) / 1e12, 2)
+        r["executed_tiles"] = tot_done
+        r["effective_tflops"] = round(tot_done * FT / (wall_ms * 1e-3) / 1e12, 2)
         dense_tiles = int(C.tiles_dense(self.N).sum()) * self.Hq
         r["sparsity_vs_causal"] = round(1.0 - tot_tiles / dense_tiles, 4)
         return r
@@ -231,10 +248,12 @@ def vs_budget_sweep(L, o_dense, reps=3):
                 ti.reset(); ta.reset()
         torch.cuda.synchronize()
         tiles = int(C.vs_index_tiles(idx, N).sum())
+        done = int(C.vs_index_steps(idx, N).sum()) / 2.0
         ms_a = float(np.median(ta.ms()))
         e = {"setting": label, "nv": nv, "ns": ns, "index_ms": round(float(np.median(ti.ms())), 4),
-             "attn_ms": round(ms_a, 4), "tiles": tiles,
-             "tflops": round(tiles * FT / ms_a / 1e9, 2),
+             "attn_ms": round(ms_a, 4), "tiles": tiles, "executed_tiles": done,
+             "tflops": round(done * FT / ms_a / 1e9, 2),
+             "frac_of_bf16_peak": round(done * FT / ms_a / 1e9 / PEAK_BF16_TFLOPS, 4),
              "sparsity_vs_causal": round(1.0 - tiles / dense_tiles, 4)}
         if o_dense is not None:
             e["output_rel_l2_vs_dense"] = output_distance(L.o, o_dense, heads)
@@ -279,9 +298,12 @@ def short_context(lengths=(8192, 16384, 32768, 65536), reps=5):
 
 
 def cpu_baseline(layer, budget_s=20.0):
-    """The CPU oracle, as it stands, on a bounded sample of the workload:
-    one Vertical-Slash head's index build in full, then attention on sampled
-    64-row query blocks of that head, until ~budget_s of CPU time is used."""
+    """The CPU oracle, as it stands, on a bounded sample of the workload.  Every head pattern of
+    the layer is sampled on its own -- the index build of one head (Vertical-Slash: in full;
+    Block-Sparse: the pooling in full, block logits and top-k of sampled rows) and masked fp64
+    attention on 64-row query blocks drawn uniformly over the sequence -- with a share of the
+    time budget in proportion to the pattern's head count, and scaled linearly to the pattern's
+    heads and the layer's query blocks."""
     from oracle import minference_oracle as O
     try:
         from threadpoolctl import threadpool_info
@@ -289,43 +311,87 @@ def cpu_baseline(layer, budget_s=20.0):
     except Exception:
         cores = os.cpu_count() or 1
     c, N = layer.cfg, layer.N
-    if layer.vs_heads:
-        h = layer.vs_heads[0]
-        Qh, Kh, Vh = layer.x.head_f64(h)
-        t0 = time.perf_counter()
-        Vi, Si, _, _ = O.vs_index(Qh, Kh, c["last_q"], c["nv"], c["ns"])
-        t_index = time.perf_counter() - t0
-        attend = lambda i0: O.vs_attention(Qh, Kh, Vh, Vi, Si, i0, i0 + 64)
-        n_index_heads = len(layer.vs_heads)
-    else:
-        h = (layer.a_heads or layer.bs_heads)[0]
-        Qh, Kh, Vh = layer.x.head_f64(h)
-        t_index, n_index_heads = 0.0, 0
-        if layer.a_heads:
-            attend = lambda i0: O.ashape_attention(Qh, Kh, Vh, c["n_init"], c["n_local"], i0, i0 + 64)
-        else:
-            t0 = time.perf_counter()
-            bi, bc, _ = O.bs_index(Qh, Kh, 64, c["topk"])
-            t_index, n_index_heads = time.perf_counter() - t0, len(layer.bs_heads)
-            attend = lambda i0: O.bs_attention(Qh, Kh, Vh, bi, bc, i0, i0 + 64)
     NB = N // 64
     rng = np.random.default_rng(7)
-    blocks, t_attn = [], 0.0
-    while t_attn + t_index < budget_s and len(blocks) < 64:
-        b = int(rng.integers(NB // 2, NB))
-        t0 = time.perf_counter()
-        attend(b * 64)
-        t_attn += time.perf_counter() - t0
-        blocks.append(b)
-    # linear extrapolation to the layer: index per head, attention per query block
-    n_blocks_layer = NB * layer.Hq
-    est_ms = (t_index * n_index_heads + t_attn / len(blocks) * n_blocks_layer) * 1e3
-    return {"value": round(est_ms, 1), "unit": "ms/layer (extrapolated)", "cores": int(cores),
-            "kind": "oracle",
-            "sample": (f"{layer.name}: oracle index build of 1 head ({t_index:.2f}s) + masked fp64 attention of "
-                       f"{len(blocks)} sampled 64-row query blocks of that head ({t_attn:.2f}s), "
-                       f"scaled to {n_index_heads} index heads and {n_blocks_layer} query blocks"),
-            "measured_s": round(t_index + t_attn, 2)}
+    groups = [(k, h) for k, h in (("vs", layer.vs_heads), ("bs", layer.bs_heads), ("ashape", layer.a_heads)) if h]
+    n_all = sum(len(h) for _, h in groups)
+    est_ms, measured, notes = 0.0, 0.0, []
+    for kind, heads in groups:
+        share = max(budget_s * len(heads) / n_all, 1.5)
+        Qh, Kh, Vh = layer.x.head_f64(heads[0])
+        t_index = t_index_measured = 0.0
+        if kind == "vs":
+            t0 = time.perf_counter()
+            Vi, Si, _, _ = O.vs_index(Qh, Kh, c["last_q"], c["nv"], c["ns"])
+            t_index = t_index_measured = time.perf_counter() - t0
+            attend = lambda b: O.vs_attention(Qh, Kh, Vh, Vi, Si, 64 * b, 64 * b + 64)
+            idx_note = f"index of 1 head in full {t_index:.2f}s"
+        elif kind == "bs":
+            t0 = time.perf_counter()
+            Qp, Kp = O.bs_pool(Qh), O.bs_pool(Kh)
+            t_pool = time.perf_counter() - t0
+            tau = 1.0 / math.sqrt(Qh.shape[1])
+            bi = -np.ones((NB, c["topk"]), dtype=np.int64)
+            bc = np.zeros(NB, dtype=np.int64)
+
+            def index_row(b):                    # Alg. 3 for one query block: block logits, top-k
+                sel = O.topk_indices((Qp[b] @ Kp[:b + 1].T) * tau, c["topk"])
+                bi[b, :sel.size], bc[b] = sel, sel.size
+
+            t_rows, rows = 0.0, []
+            while t_rows < share / 4 and len(rows) < 256:
+                b = int(rng.integers(0, NB))
+                t0 = time.perf_counter()
+                index_row(b)
+                t_rows += time.perf_counter() - t0
+                rows.append(b)
+            t_index = t_pool + t_rows / len(rows) * NB     # scaled to all rows
+            t_index_measured = t_pool + t_rows
+
+            def attend(b):
+                if bc[b] == 0:
+                    index_row(b)
+                return O.bs_attention(Qh, Kh, Vh, bi, bc, 64 * b, 64 * b + 64)
+            idx_note = f"pooling in full {t_pool:.2f}s + {len(rows)} index rows {t_rows:.2f}s (scaled to {NB} rows)"
+        else:
+            attend = lambda b: O.ashape_attention(Qh, Kh, Vh, c["n_init"], c["n_local"], 64 * b, 64 * b + 64)
+            idx_note = "no index"
+        t_attn, blocks = 0.0, []
+        while t_attn + (t_index if kind == "vs" else 0.0) < share and len(blocks) < 64:
+            b = int(rng.integers(0, NB))
+            t0 = time.perf_counter()
+            attend(b)
+            t_attn += time.perf_counter() - t0
+            blocks.append(b)
+        measured += t_index_measured + t_attn
+        est_ms += (t_index + t_attn / len(blocks) * NB) * len(heads) * 1e3
+        notes.append(f"{kind} x{len(heads)}: {idx_note}, attention of {len(blocks)} blocks {t_attn:.2f}s")
+        del Qh, Kh, Vh
+    return {"value": round(est_ms, 1), "unit": "ms/layer (extrapolated)", "cores": int(cores), "kind": "oracle",
+            "sample": f"{layer.name}: " + "; ".join(notes) + f"; each scaled to its heads and {NB} query blocks per head",
+            "measured_s": round(measured, 2)}
+
+
+def device_peak():
+    """The bf16 dense MFMA peak derived from what the device reports: compute units x 4 SIMDs x
+    1024 FLOP per SIMD and clock (v_mfma_f32_32x32x16_bf16: 32768 FLOP in 8 passes of 4 clocks)
+    x the maximum engine clock.  roofline.frac divides by the published 2.5 PFLOP/s."""
+    p = torch.cuda.get_device_properties(0)
+    cus, mhz = int(p.multi_processor_count), float(p.clock_rate) / 1e3
+    return {"device": p.name, "compute_units": cus, "max_engine_clock_mhz": round(mhz, 1),
+            "flop_per_clock_per_cu": 4096,
+            "derived_bf16_tflops": round(cus * 4096 * mhz * 1e6 / 1e12, 1),
+            "published_bf16_tflops": PEAK_BF16_TFLOPS}
+
+
+def roofline_of(rep, workload):
+    """Roofline entry of a layer report: its attention call with the largest time."""
+    dom = max((k for k in rep["calls"] if "tiles" in rep["calls"][k]), key=lambda k: rep["calls"][k]["ms"])
+    d = rep["calls"][dom]
+    return {"bound": "mfma", "kernel": dom, "achieved": d["tflops"], "peak": PEAK_BF16_TFLOPS,
+            "unit": "TFLOP/s", "frac": round(d["tflops"] / PEAK_BF16_TFLOPS, 4),
+            "traffic": read_traffic(f"{dom}:{workload}"),
+            "flops_per_launch": d["executed_tiles"] * FT, "avg_launch_ms": d["ms"]}
 
 
 def read_traffic(kernel_tag):
@@ -383,6 +449,7 @@ def main():
             L = Layer(name)
             wall = L.run(max(a.steps, 3), a.warmup)
             at128[name] = L.report(wall)
+            at128[name]["roofline"] = roofline_of(at128[name], name)
             log(name, json.dumps(at128[name]))
             o_dense = None
             if not a.no_dense:
@@ -413,13 +480,10 @@ def main():
     rep = L.report(wall)
     log(a.workload, json.dumps(rep))
 
-    # dominant kernel = the attention call with the most tiles
-    dom = max((k for k in rep["calls"] if "tiles" in rep["calls"][k]), key=lambda k: rep["calls"][k]["ms"])
-    d = rep["calls"][dom]
-    roofline = {"bound": "mfma", "kernel": dom, "achieved": d["tflops"], "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(d["tflops"] / PEAK_BF16_TFLOPS, 4),
-                "traffic": read_traffic(f"{dom}:{a.workload}"),
-                "flops_per_launch": d["tiles"] * FT, "avg_launch_ms": d["ms"]}
+    # dominant kernel = the attention call with the largest time
+    roofline = roofline_of(rep, a.workload)
+    roofline["peak_derivation"] = device_peak()
+    log("peak", json.dumps(roofline["peak_derivation"]))
 
     if not a.no_dense:
         if L.N > 262144:

@@ -288,11 +288,16 @@ def tiles_bs(blk_cnt):
     return np.asarray(blk_cnt, dtype=np.int64).copy()
 
 
-def tiles_vs(N, V_idx, S_idx, B=64):
+def tiles_vs(N, V_idx, S_idx, B=64, W=None):
     """Slash part: the cover of block b, as maximal runs of permitted keys in
     [0, bB + B), costs ceil(len / B) tiles per run.  Column part: causal
-    verticals (v < bB + B) outside that cover, B per gathered tile."""
+    verticals (v < bB + B) outside that cover, B per gathered tile.
+    With W given the unit is a step of B query rows x W keys instead of a
+    B x B tile (a kernel that walks runs W keys at a time computes
+    ceil(len / W) steps per run, which is less work than ceil(len / B) tiles
+    whenever len mod B is in 1 .. B - W)."""
     NB = N // B
+    W = B if W is None else W
     cover = slash_cover(S_idx, N, B)
     V_idx = np.asarray(V_idx, dtype=np.int64)
     out = np.zeros(NB, dtype=np.int64)
@@ -302,8 +307,8 @@ def tiles_vs(N, V_idx, S_idx, B=64):
         c = cover[np.clip(t, -B, N - 1) + B]
         edges = np.diff(np.concatenate([[0], c.astype(np.int8), [0]]))
         starts, ends = np.flatnonzero(edges == 1), np.flatnonzero(edges == -1)
-        n_slash = int(np.sum(-(-(ends - starts) // B)))
+        n_slash = int(np.sum(-(-(ends - starts) // W)))
         v = V_idx[V_idx < b * B + B]
         free = int(np.sum(~c[v])) if v.size else 0
-        out[b] = n_slash + -(-free // B)
+        out[b] = n_slash + -(-free // W)
     return out

@@ -43,8 +43,15 @@ def tiles_bs(blk_cnt):
     return np.asarray(blk_cnt, dtype=np.int64).copy()
 
 
-def tiles_vs(N, v_idx, runs):
-    """v_idx: ascending kept verticals; runs: [n, 2] offset runs [t0, t1)."""
+STEP = 32     # keys per step of the Vertical-Slash kernel (one step = 64 query rows x 32 keys)
+
+
+def tiles_vs(N, v_idx, runs, width=BLOCK):
+    """v_idx: ascending kept verticals; runs: [n, 2] offset runs [t0, t1).
+    width = 64: the canonical 64 x 64 tile count of the index.  width = 32: the 64 x 32 steps
+    the kernel executes (it walks a run 32 keys at a time from the run's first key and gathers
+    verticals 32 at a time), which is what its FLOP rate is computed from: a run of length len
+    costs ceil(len / 32) steps, less than ceil(len / 64) tiles when len mod 64 is in 1 .. 32."""
     NB = N // BLOCK
     q0 = BLOCK * np.arange(NB, dtype=np.int64)[:, None]
     runs = np.asarray(runs, dtype=np.int64).reshape(-1, 2)
@@ -54,7 +61,7 @@ def tiles_vs(N, v_idx, runs):
         ks = np.maximum(q0 - runs[None, :, 1] + 1, 0)
         ke = np.minimum(q0 - runs[None, :, 0] + 1, N)
         ln = np.maximum(ke - ks, 0)
-        out += (-(-ln // BLOCK)).sum(axis=1)
+        out += (-(-ln // width)).sum(axis=1)
     if v.size:
         for lo in range(0, NB, 1024):                       # bounded memory at 1M tokens
             hi = min(NB, lo + 1024)
@@ -66,7 +73,7 @@ def tiles_vs(N, v_idx, runs):
             else:
                 inside = np.zeros_like(causal)
             free = (causal & ~inside).sum(axis=1)
-            out[lo:hi] += -(-free // BLOCK)
+            out[lo:hi] += -(-free // width)
     return out
 
 
@@ -149,6 +156,15 @@ def vs_index_tiles(idx, N):
     v_idx = idx.v_idx.cpu().numpy()
     cover = idx.cover.cpu().numpy()
     return np.stack([tiles_vs(N, v_idx[r, :counts[r, 0]], cover[r, :counts[r, 2]])
+                     for r in range(idx.rows)])
+
+
+def vs_index_steps(idx, N):
+    """Per-head counts [rows, NB] of the 64 x 32 steps the Vertical-Slash kernel executes."""
+    counts = idx.counts.cpu().numpy()
+    v_idx = idx.v_idx.cpu().numpy()
+    cover = idx.cover.cpu().numpy()
+    return np.stack([tiles_vs(N, v_idx[r, :counts[r, 0]], cover[r, :counts[r, 2]], width=STEP)
                      for r in range(idx.rows)])
 
 

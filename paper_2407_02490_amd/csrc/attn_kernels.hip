@@ -31,8 +31,9 @@
 //    result is identical up to rounding because m cancels in O / l.  No
 //    per-step row max, no rescale of the 128 O registers, no branch on data.
 //    If a row sum ends up >= 2^100 or non-finite (logits that outgrow the first
-//    step's max by more than ~69 nats), the whole query block is redone with
-//    the exact two-pass scheme: pass 1 finds every row max, pass 2 accumulates.
+//    step's max by more than ~69 nats) or below 2^-100 (every term underflowed:
+//    logits far below the reference), the whole query block is redone with the
+//    exact two-pass scheme: pass 1 finds every row max, pass 2 accumulates.
 //  * Three tiles in flight per loop iteration: logits of tile t+1, softmax of
 //    tile t, output update of tile t-1.  With one wave per SIMD (the kernels
 //    need about 450 registers) the wave issues one instruction every four
@@ -59,6 +60,7 @@ namespace minf {
 
 constexpr int VCAP = 1024;               // compacted vertical columns held in LDS per round
 constexpr float L_LIMIT = 1.2676506e30f;  // 2^100: beyond it the optimistic pass is redone exactly
+constexpr float L_TINY = 7.888609e-31f;   // 2^-100: below it too (underflow of every term of a row)
 
 struct WaveState {
   bf16x8 q[2][8];     // Q fragments: [query half nb][k step]: Q[32nb + n][16ks + 8h ..]
@@ -500,13 +502,19 @@ __device__ inline void gathered_step(WaveState &st, bool &has_ref, const LaneOfs
 }
 
 // After the optimistic pass: true (wave-uniform) if some row of the wave must be
-// redone exactly.
+// redone exactly: its sum overflowed (logits far above the reference), or it is
+// zero or nearly so.  The latter happens to a row whose reference stayed at the
+// neutral 0 (no permitted key in the wave's first step) or far above its own
+// logits while all of them lie below about -100 in the base-2 domain: p then
+// flushes to zero although the row is well defined under Eq. 1.  A row that
+// really has no permitted key also takes the exact pass (and ends with zeros);
+// only Vertical-Slash blocks before the first kept line have such rows.
 __device__ inline bool needs_exact(const WaveState &st) {
   bool bad = false;
 #pragma unroll
   for (int nb = 0; nb < 2; ++nb) {
     const float l = st.l[nb] + __shfl_xor(st.l[nb], 32);
-    bad = bad || !(l < L_LIMIT);
+    bad = bad || !(l < L_LIMIT) || l < L_TINY;
   }
   return __builtin_amdgcn_ballot_w64(bad) != 0;
 }

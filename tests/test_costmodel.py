@@ -34,6 +34,20 @@ def test_vs_tiles_match_oracle(seed):
     assert np.array_equal(C.tiles_vs(N, V, runs_of(S, N)), O.tiles_vs(N, V, S))
 
 
+@pytest.mark.parametrize("seed", [3, 4])
+def test_vs_executed_steps_match_oracle(seed):
+    """The 64 x 32 steps the Vertical-Slash kernel executes (what its FLOP rate is computed from):
+    never more than two per canonical tile, fewer whenever a run's length mod 64 is in 1 .. 32."""
+    rng = np.random.default_rng(seed)
+    N = 4096
+    V = np.sort(rng.choice(N, 300, replace=False))
+    S = np.sort(np.concatenate([np.arange(0, 90), rng.choice(np.arange(200, N), 60, replace=False)]))
+    steps = C.tiles_vs(N, V, runs_of(S, N), width=C.STEP)
+    assert np.array_equal(steps, O.tiles_vs(N, V, S, 64, 32))
+    tiles = C.tiles_vs(N, V, runs_of(S, N))
+    assert np.all(steps <= 2 * tiles) and steps.sum() < 2 * tiles.sum()
+
+
 def test_vs_tiles_edge_cases():
     N = 1024
     assert np.array_equal(C.tiles_vs(N, [], runs_of(np.array([0]), N)), O.tiles_vs(N, [], [0]))

@@ -387,3 +387,36 @@ def test_exact_two_pass_fallback(B):
     for h in (0, 1):
         want = O.vs_attention(to_f64(q[h]), to_f64(k[0]), to_f64(v[0]), Vl, Sl, Bm=64)
         assert_close_rows(o[h], want, f"fallback vs head {h}")
+
+
+def test_exact_fallback_on_underflow(B):
+    """Strongly negative logits (every key nearly opposite to every query): a row whose exponent
+    reference is the neutral 0 -- no permitted key in the first step its wave computes -- would
+    flush every term to zero; the kernels must notice the vanishing row sum and redo the block
+    exactly.  That is A-shape without sink and with a window shorter than a workgroup's rows (the
+    last wave's rows see nothing in the workgroup's first tile); Vertical-Slash and Block-Sparse
+    rows always find a key in their first step and are checked here for the extreme logits only."""
+    N = 1024
+    g = torch.Generator().manual_seed(77)
+    u = torch.randn(128, generator=g)
+    u = u / u.norm() * (128 ** 0.5)
+    q = (u + 0.3 * torch.randn(2, N, 128, generator=g)).to(torch.bfloat16).cuda()
+    k = (-14.0 * u + 0.3 * torch.randn(1, N, 128, generator=g)).to(torch.bfloat16).cuda()
+    v = torch.randn(1, N, 128, generator=g).to(torch.bfloat16).cuda()
+    # logits are about -14 * 128 / sqrt(128) = -158 nats = -228 in the base-2 domain
+    assert float((q[0, 100].float() @ k[0, 50].float()) / 128 ** 0.5) < -120
+    o = run_heads(B.minf_ashape_attn, q, k, v, [0, 1], 0, 65)
+    for h in (0, 1):
+        want = O.ashape_attention(to_f64(q[h]), to_f64(k[0]), to_f64(v[0]), 0, 65)
+        assert np.abs(want).max() > 0.1
+        assert_close_rows(o[h], want, f"underflow A-shape head {h}")
+    Vl, Sl = [3, 500], [0, 200, 201, 700]
+    dev = B.vs_index_from_host([Vl, Vl], [Sl, Sl], N)
+    o = run_heads(B.minf_vs_attn, q, k, v, [0, 1], dev)
+    for h in (0, 1):
+        want = O.vs_attention(to_f64(q[h]), to_f64(k[0]), to_f64(v[0]), Vl, Sl, Bm=64)
+        assert_close_rows(o[h], want, f"underflow VS head {h}")
+    idx, cnt = np.array([[[0, -1]] + [[0, b] for b in range(1, 16)]]), np.array([[1] + [2] * 15])
+    devb = B.bs_index_from_host(idx, cnt)
+    o = run_heads(B.minf_bs_attn, q, k, v, [0], devb)
+    assert_close_rows(o[0], O.bs_attention(to_f64(q[0]), to_f64(k[0]), to_f64(v[0]), idx[0], cnt[0]), "underflow BS")

@@ -228,6 +228,35 @@ def test_vs_empty_rows_when_nothing_selected():
     assert not m[:8].any()
 
 
+def test_tiles_vs_bruteforce_per_block_also_in_narrower_key_steps(rng):
+    """tiles_vs against sets built slash by slash for every block (pure python), in B x B tiles
+    and in B x W steps (W < B: the unit of a kernel that walks a run W keys at a time)."""
+    N, B = 96, 8
+    for trial in range(6):
+        S = sorted(rng.choice(N, int(rng.integers(1, 12)), replace=False).tolist())
+        V = sorted(rng.choice(N, int(rng.integers(0, 20)), replace=False).tolist())
+        for W in (8, 4, 2):
+            want = []
+            for b in range(N // B):
+                keys = set()
+                for o in S:
+                    keys |= {j for j in range(b * B - o, b * B - o + B) if 0 <= j < b * B + B}
+                n, j = 0, 0
+                while j < b * B + B:                       # maximal runs of covered keys
+                    if j in keys:
+                        e = j
+                        while e in keys:
+                            e += 1
+                        n += -(-(e - j) // W)
+                        j = e
+                    else:
+                        j += 1
+                free = sum(1 for v in V if v < b * B + B and v not in keys)
+                want.append(n + -(-free // W))
+            got = O.tiles_vs(N, V, S, B, W) if W != B else O.tiles_vs(N, V, S, B)
+            assert list(got) == want, (trial, W)
+
+
 def test_tiles_vs_bounds_and_closed_form(rng):
     N, B = 256, 16
     # contiguous slashes 0..w-1: cover (-B, w-1] in offsets -> one run of
