@@ -15,6 +15,8 @@
 // Top-k is an exact radix select on the order-preserving integer image of the
 // fp32 score (4 passes of 8 bits), ties to the lower index, followed by an
 // ordered compaction, so the kept indices come out ascending without a sort.
+#include <string.h>
+
 #include "mfma_tile.h"
 
 namespace minf {
@@ -27,6 +29,16 @@ struct KvMap {                      // pooling work list of the Block-Sparse bui
   int32_t n_kv;                     // distinct KV heads used by the call
   int32_t kv[MINF_MAX_HEADS];       // their ids
   int32_t slot_kv[MINF_MAX_HEADS];  // head slot -> position in kv[]
+};
+
+// Work list of the Vertical-Slash score kernels: the listed query heads grouped by the K/V
+// head they read, at most four per group (one wave each).  The waves of a group share every K
+// tile, so K is streamed once per group and pass instead of once per query head.
+constexpr int VS_GROUP = 4;
+struct VsGroups {
+  int32_t n;                                  // groups
+  uint8_t cnt[MINF_MAX_HEADS];                // query heads in the group (1 .. VS_GROUP)
+  uint8_t slot[MINF_MAX_HEADS][VS_GROUP];     // their list slots
 };
 
 // ---------------------------------------------------------------------------
@@ -313,12 +325,15 @@ __device__ inline void block_scan2_256(int a, int b, int *ea, int *eb, int *ta, 
 
 // ---------------------------------------------------------------------------
 // Vertical-Slash score kernels.  Estimating row r (0..63) is query N-64+r; rows
-// r < 64 - last_q do not take part.  Workgroup (head slot, chunk c), one wave,
-// owns the offsets [cC, cC+C) and the keys [N-cC-C, N-cC): tile m of the chunk
-// holds the keys [N-cC-64(m+1), N-cC-64m); offsets of the chunk meet only tiles
-// 0..C/64.  K tiles arrive by direct global -> LDS loads into two buffers (the
-// swizzled layout of the attention kernels), the next tile in flight while the
-// current one is reduced.
+// r < 64 - last_q do not take part.  Workgroup (group of query heads that read
+// one K/V head, chunk c): four waves, one per query head of the group (a wave
+// without a head only helps to fetch).  It owns the offsets [cC, cC+C) and the
+// keys [N-cC-C, N-cC): tile m of the chunk holds the keys [N-cC-64(m+1),
+// N-cC-64m); offsets of the chunk meet only tiles 0..C/64.  K tiles arrive by
+// direct global -> LDS loads into three buffers (the swizzled layout of the
+// attention kernels), a quarter per wave, the next tile in flight while the
+// current one is reduced; one barrier per tile.  The tile is fetched once for
+// the whole group: K is streamed once per K/V head and pass.
 //  pass 1: S^T = K Q^T (keys along the accumulator registers): running row max
 //          and row sum stay inside a lane.
 //  pass 2: S = Q K^T (keys along the lanes, estimating rows along the
@@ -328,27 +343,83 @@ __device__ inline void block_scan2_256(int a, int b, int *ea, int *eb, int *ta, 
 //          that a diagonal is a column: every lane then adds up two columns.
 //          Positions the skew never writes hold zeros from the start, so no
 //          bounds are tested.  (LDS float atomics were tried for this and cost
-//          about 700 cycles per instruction.)  One wave, program order: the
-//          sums are reproducible.  The 64 x N estimate is never stored.
+//          about 700 cycles per instruction.)  One wave per head, program
+//          order: the sums are reproducible.  The 64 x N estimate is never stored.
 // ---------------------------------------------------------------------------
 constexpr int VS_TILE_BYTES = TILE_BYTES;          // 16 KiB
 constexpr int VS_DPAD = 96;                       // slack on both sides of the chunk's diagonal sums
 constexpr int VS_SKEW_PITCH = 64;                 // floats per row of the skewed probability tile (32 rows x 32 keys)
+constexpr int VS_WAVE_FLOATS = VS_CHUNK + 2 * VS_DPAD + 32 * VS_SKEW_PITCH;   // pass 2, private to a wave
+
+// This wave's quarter of a K tile of ROWS rows (64 or 32) that lies wholly inside [0, N).
+template <int ROWS>
+__device__ inline void vs_fetch_quarter(const bf16_t *kh, int64_t k_st, const DmaLane &dl, int kbase, char *tile,
+                                        int wave) {
+  constexpr int PER = ROWS / 4 / VS_GROUP;          // 1 KiB blocks per wave: 4 or 2
+  const bf16_t *ubase = kh + (int64_t)kbase * k_st;
+  const unsigned base = lds_addr_of(tile);
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int blk = wave * PER + i;
+    // block blk takes the lane offsets of blk % 4: i for whole groups of four, 2 (wave % 2) + i for pairs
+    const unsigned voff = PER == 4 ? dl.voff[i] : ((wave & 1) ? dl.voff[2 + i] : dl.voff[i]);
+    dma16_su(ubase + (int64_t)(4 * blk) * k_st, voff, base + blk * 1024);
+  }
+}
+
+// Adds the diagonal sums of a 32 x 32 tile of probabilities to dbase[-63 .. 0].  p[r] is the
+// element (local row rl = 8 (r / 4) + 4 h + r % 4, key column n) of this lane (n = lane % 32,
+// h = lane / 32).  The tile goes to LDS skewed, element (rl, n) at column n - rl + 32, so that a
+// diagonal is a column; column j belongs to dbase[-j].  Lane (cp = n, rh = h) then adds up the
+// columns 2 cp, 2 cp + 1 over the rows 16 rh .. 16 rh + 15 (8-byte reads) and the two row halves
+// meet in the lanes rh = 0.  Positions the skew never writes hold zeros from the start.  One wave,
+// program order: reproducible.
+__device__ inline void vs_skew_reduce(const float (&p)[16], float *skew, float *dbase, int n, int h) {
+  float *wlane = skew + 4 * h * (VS_SKEW_PITCH - 1) + n + 32;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) wlane[(8 * (r >> 2) + (r & 3)) * (VS_SKEW_PITCH - 1)] = p[r];
+  // (LDS operations of one wave execute in order; the fences are for the compiler)
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  const float2 *col2 = reinterpret_cast<const float2 *>(skew + 16 * h * VS_SKEW_PITCH) + n;
+  float t0 = 0.f, t1 = 0.f;
+#pragma unroll
+  for (int rl = 0; rl < 16; ++rl) {
+    const float2 e = col2[rl * (VS_SKEW_PITCH / 2)];
+    t0 += e.x;
+    t1 += e.y;
+  }
+  const float u0 = __shfl_xor(t0, 32), u1 = __shfl_xor(t1, 32);
+  if (h == 0) {
+    dbase[-2 * n] += t0 + u0;          // column 2 n
+    dbase[-2 * n - 1] += t1 + u1;      // column 2 n + 1
+  }
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
 template <int PASS>
-__global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int last_q, int n_chunks,
-                                                      float *ml_part, const float *ml_fin,
-                                                      float *colsum, float *diagsum) {
+__global__ __launch_bounds__(256, 2) void vs_score_kernel(QKV x, HeadList hl, VsGroups vg, int last_q, int n_chunks,
+                                                       float *ml_part, const float *ml_fin,
+                                                       float *colsum, float *diagsum) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  // pass 1: two 64-key K tiles.  pass 2: two 32-key K half tiles, the diagonal sums, the skewed tile.
-  float *dacc = reinterpret_cast<float *>(lds + 2 * HALF_BYTES);       // [VS_DPAD + VS_CHUNK + VS_DPAD], pass 2
+  // pass 1: three shared 64-key K tiles.  pass 2: three shared 32-key K half tiles, then per wave
+  // the diagonal sums and the skewed tile.
+  const int grp = blockIdx.y, chunk = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const bool active = wave < vg.cnt[grp];
+  // a wave without a head takes the group's first one for its addresses; it only helps to fetch
+  const int slot = __builtin_amdgcn_readfirstlane((int)vg.slot[grp][active ? wave : 0]);
+  float *dacc = reinterpret_cast<float *>(lds + 3 * HALF_BYTES) + wave * VS_WAVE_FLOATS;   // [VS_DPAD + VS_CHUNK + VS_DPAD], pass 2
   float *skew = dacc + VS_CHUNK + 2 * VS_DPAD;                         // [32][VS_SKEW_PITCH], pass 2
 
-  const int slot = blockIdx.y, chunk = blockIdx.x;
   const int head = __builtin_amdgcn_readfirstlane(hl.h[slot]);
   const int kvh = to_sgpr(head / x.group);
   const bf16_t *qh = x.q + head * x.q_sh, *kh = x.k + kvh * x.k_sh;
-  const int lane = threadIdx.x, n = lane & 31, h = lane >> 5;
+  const int n = lane & 31, h = lane >> 5;
   const int N = x.N, C = VS_CHUNK;
   const int r_min = 64 - last_q;
 
@@ -390,19 +461,22 @@ __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int la
     // 64-key tiles, two 16 KiB buffers; tiles are 64-aligned: wholly inside [0, N) or outside
     const int n_tiles = min(C / 64, key_hi / 64);
     auto tile_key = [&](int mm) { return key_hi - 64 * (mm + 1); };
+    // three buffers, two tiles in flight: tile i lives in buffer i mod 3
     auto fetch = [&](int mm) {
-      dma_rows<1, 64, true>(kh, x.k_st, dl, tile_key(mm), nullptr, N, lds + (mm & 1) * VS_TILE_BYTES, 0, lane);
+      vs_fetch_quarter<64>(kh, x.k_st, dl, tile_key(mm), lds + (mm % 3) * VS_TILE_BYTES, wave);
     };
     if (n_tiles > 0) fetch(0);
+    if (n_tiles > 1) fetch(1);
     for (int m = 0; m < n_tiles; ++m) {
       const int kt = tile_key(m);
-      const char *tK = lds + (m & 1) * VS_TILE_BYTES;
-      if (m + 1 < n_tiles) {
-        fetch(m + 1);
-        MINF_WAIT_VMCNT(16);
-      } else {
-        MINF_WAIT_VMCNT(0);
-      }
+      const char *tK = lds + (m % 3) * VS_TILE_BYTES;
+      // Tile m has landed once every wave has waited for its quarter (its own four loads of tile
+      // m+1 may stay in flight).  Behind the barrier every wave is also done with tile m-1, whose
+      // buffer the fetch of tile m+2 overwrites.
+      if (m + 1 < n_tiles) MINF_WAIT_VMCNT(4); else MINF_WAIT_VMCNT(0);
+      __syncthreads();
+      if (m + 2 < n_tiles) fetch(m + 2);
+      if (!active) continue;                         // a wave without a head only fetches
       const bool diag_tile = kt + 63 > N - 64;       // only the last 64 keys are cut by causality
       f32x16 s[2][2];
 #pragma unroll
@@ -467,8 +541,6 @@ __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int la
         l_run = l_run * fast_exp2(m_run - m_use) + sum;
         m_run = m_new;
       }
-      // the LDS reads of this tile are complete (their data was consumed) before the tile
-      // after next overwrites the buffer: that fetch is issued in the next iteration
     }
   } else {
     // 32-key half tiles, two 8 KiB buffers.  The offsets of the chunk meet the half tiles
@@ -476,22 +548,28 @@ __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int la
     const int n_half = min(C / 32 + 2, key_hi / 32);
     auto tile_key = [&](int mm) { return key_hi - 32 * (mm + 1); };
     auto fetch = [&](int mm) {
-      dma_rows<1, 32, true>(kh, x.k_st, dl, tile_key(mm), nullptr, N, lds + (mm & 1) * HALF_BYTES, 0, lane);
+      vs_fetch_quarter<32>(kh, x.k_st, dl, tile_key(mm), lds + (mm % 3) * HALF_BYTES, wave);
     };
     // lane (n, h) reads K row n of the half tile: keys run along the lanes in index order
     int kofs[8];
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) kofs[ks] = swz_byte(n, 2 * ks + h);
+    float carry[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) carry[r] = 0.f;
     if (n_half > 0) fetch(0);
+    if (n_half > 1) fetch(1);
     for (int m = 0; m < n_half; ++m) {
       const int kt = tile_key(m);
-      const char *tK = lds + (m & 1) * HALF_BYTES;
-      if (m + 1 < n_half) {
-        fetch(m + 1);
-        MINF_WAIT_VMCNT(8);
-      } else {
-        MINF_WAIT_VMCNT(0);
-      }
+      const char *tK = lds + (m % 3) * HALF_BYTES;
+      // As in pass 1: three buffers, one barrier per half tile.  At most the two youngest memory
+      // operations of this wave may stay in flight; whatever they are (the two loads of half tile
+      // m+1, or one of them and the column-sum store of the iteration before), half tile m is
+      // older and has landed.
+      if (m + 1 < n_half) MINF_WAIT_VMCNT(2); else MINF_WAIT_VMCNT(0);
+      __syncthreads();
+      if (m + 2 < n_half) fetch(m + 2);
+      if (!active) continue;
       const bool diag_tile = kt + 31 > N - 64;
       // s[nb]: register r holds row 32 nb + 8 (r / 4) + 4 h + r % 4, key kt + n
       f32x16 s[2];
@@ -505,31 +583,41 @@ __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int la
         s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[0][ks], kf, s[0], 0, 0, 0);
         s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(q[1][ks], kf, s[1], 0, 0, 0);
       }
+      // probabilities of the half tile: pv[nb][r] for row 32 nb + 8 (r / 4) + 4 h + r % 4, key kt + n
+      float pv[2][16];
       float cs = 0.f;
 #pragma unroll
       for (int nb = 0; nb < 2; ++nb) {
-        // rows 32 nb .. 32 nb + 31: local row rl = 8 (r / 4) + 4 h + r % 4, key column n;
-        // element (rl, n) goes to skew[rl][n - rl + 32]
-        float *wlane = skew + 4 * h * (VS_SKEW_PITCH - 1) + n + 32;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int rl4 = 8 * (r >> 2) + (r & 3);                    // rl - 4 h
-          float pv = fast_exp2(fmaf(s[nb][r], x.c_log2, -off[nb][r]));
-          if (diag_tile) pv = kt + n <= N - 64 + 32 * nb + rl4 + 4 * h ? pv : 0.f;
-          cs += pv;
-          wlane[rl4 * (VS_SKEW_PITCH - 1)] = pv;
+        for (int r = 0; r < 16; ++r) pv[nb][r] = fast_exp2(fmaf(s[nb][r], x.c_log2, -off[nb][r]));
+        if (diag_tile) {           // only the last two half tiles of a head are cut by causality
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int rl4 = 8 * (r >> 2) + (r & 3);                    // local row - 4 h
+            pv[nb][r] = kt + n <= N - 64 + 32 * nb + rl4 + 4 * h ? pv[nb][r] : 0.f;
+          }
         }
-        // column j of the skewed tile is the diagonal with local offset 32 (m + nb) - j
-        float t = 0.f;
-#pragma unroll 8
-        for (int rl = 0; rl < 32; ++rl) t += skew[rl * VS_SKEW_PITCH + lane];
-        dacc[VS_DPAD + 32 * (m + nb) - lane] += t;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) cs += pv[nb][r];
       }
+      // Diagonal sums.  Element (row 32 + rl, key kt + n) of this half tile and element (row rl,
+      // key kt - 32 + n) of the next one lie on the same diagonal and in the same register and
+      // lane, so the upper 32 rows wait one iteration (carry) and go through LDS together with the
+      // lower 32 rows of the next half tile: one skewed tile per half tile instead of two.
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float both = pv[0][r] + carry[r];
+        carry[r] = pv[1][r];
+        pv[0][r] = both;
+      }
+      vs_skew_reduce(pv[0], skew, dacc + VS_DPAD + 32 * m, n, h);
       // the two lane halves hold the two halves of the rows of the same key
       const float other = __shfl_xor(cs, 32);
       const float tot = h == 0 ? cs + other : other + cs;   // same operand order in both
-      if (h == 0 && m < C / 32) colsum[(int64_t)slot * N + kt + n] = tot;
+      if (active && h == 0 && m < C / 32) colsum[(int64_t)slot * N + kt + n] = tot;
     }
+    // the upper rows of the last half tile
+    vs_skew_reduce(carry, skew, dacc + VS_DPAD + 32 * n_half, n, h);
   }
 
   if (PASS == 1) {
@@ -543,7 +631,7 @@ __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int la
       // same operand order in both lanes of the pair: lane-half 0's share first
       const float a = h == 0 ? l_run * fast_exp2(m_run - Mu) : lo2 * fast_exp2(mo - Mu);
       const float b = h == 0 ? lo2 * fast_exp2(mo - Mu) : l_run * fast_exp2(m_run - Mu);
-      if (h == 0) {
+      if (active && h == 0) {
         float *dst = ml_part + (((int64_t)slot * n_chunks + chunk) * 64 + 32 * nb + n) * 2;
         dst[0] = M;
         dst[1] = a + b;
@@ -553,7 +641,7 @@ __global__ __launch_bounds__(64) void vs_score_kernel(QKV x, HeadList hl, int la
     __syncthreads();
     for (int i = lane; i < C; i += 64) {
       const int o = chunk * C + i;
-      if (o < N) diagsum[(int64_t)slot * N + o] = dacc[VS_DPAD + i];
+      if (active && o < N) diagsum[(int64_t)slot * N + o] = dacc[VS_DPAD + i];
     }
   }
 }
@@ -982,14 +1070,28 @@ hipError_t launch_build_vs(const QKV &x, const HeadList &hl, int last_q, int nv,
   float *diagsum = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * N * sizeof(float));
   float *ml_part = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * nc * 128 * sizeof(float));
   float *ml_fin = reinterpret_cast<float *>(p);
-  // 32 KiB and 29 KiB per one-wave workgroup: five workgroups per CU
-  const size_t lds1 = 2 * VS_TILE_BYTES;
-  const size_t lds2 = 2 * HALF_BYTES + (VS_CHUNK + 2 * VS_DPAD + 32 * VS_SKEW_PITCH) * sizeof(float);
-  const dim3 grid(nc, hl.n);
-  hipLaunchKernelGGL(vs_score_kernel<1>, grid, dim3(64), lds1, st, x, hl, last_q, nc, ml_part,
+  // the listed heads grouped by K/V head, in order of first appearance, at most four per group
+  VsGroups vg;
+  memset(&vg, 0, sizeof(vg));
+  int gkv[MINF_MAX_HEADS];
+  for (int i = 0; i < hl.n; ++i) {
+    const int kv = hl.h[i] / x.group;
+    int g = 0;
+    while (g < vg.n && !(gkv[g] == kv && vg.cnt[g] < VS_GROUP)) ++g;
+    if (g == vg.n) { gkv[g] = kv; ++vg.n; }
+    vg.slot[g][vg.cnt[g]++] = (uint8_t)i;
+  }
+  // 48 KiB (three workgroups of four waves per CU; registers allow two) and 75 KiB (two per CU)
+  const size_t lds1 = 3 * VS_TILE_BYTES;
+  const size_t lds2 = 3 * HALF_BYTES + VS_GROUP * VS_WAVE_FLOATS * sizeof(float);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(vs_score_kernel<2>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
+  if (e != hipSuccess) return e;
+  const dim3 grid(nc, vg.n);
+  hipLaunchKernelGGL(vs_score_kernel<1>, grid, dim3(256), lds1, st, x, hl, vg, last_q, nc, ml_part,
                      (const float *)nullptr, (float *)nullptr, (float *)nullptr);
   hipLaunchKernelGGL(vs_combine_kernel, dim3(hl.n), dim3(1024), 0, st, nc, (const float *)ml_part, ml_fin);
-  hipLaunchKernelGGL(vs_score_kernel<2>, grid, dim3(64), lds2, st, x, hl, last_q, nc, (float *)nullptr,
+  hipLaunchKernelGGL(vs_score_kernel<2>, grid, dim3(256), lds2, st, x, hl, vg, last_q, nc, (float *)nullptr,
                      (const float *)ml_fin, colsum, diagsum);
   hipLaunchKernelGGL(vs_select_kernel, dim3(hl.n, 2), dim3(1024), 0, st, N, nv, ns, (const float *)colsum,
                      (const float *)diagsum, v_idx, s_idx, cover, cover_bits, counts, cover_words);
