@@ -138,7 +138,9 @@ __device__ inline void radix_select(const float *data, int n, int k, unsigned *t
 // holds four consecutive elements per 16-byte load, two loads in flight.
 template <int NT, bool VEC4>
 __device__ inline void ordered_select(const float *data, int n, unsigned thr, int take_eq, int32_t *out,
-                                      int *sh) {
+                                      int *sh, const int32_t *remap = nullptr) {
+  // remap: the value written for element i is remap[i] instead of i (data is a compacted list)
+  auto name_of = [&](int i) { return remap ? remap[i] : i; };
   constexpr int NW = NT / 64;
   constexpr int STEP = VEC4 ? 256 : 64;          // elements a wave takes per load
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -221,7 +223,7 @@ __device__ inline void ordered_select(const float *data, int n, unsigned thr, in
       int p = pos + s_scan - ns_;
 #pragma unroll
       for (int c = 0; c < 4; ++c)
-        if (sel[c]) out[p++] = i0 + 4 * lane + c;
+        if (sel[c]) out[p++] = name_of(i0 + 4 * lane + c);
       pos += s_tot;
       eq_before += e_tot;
     };
@@ -247,7 +249,7 @@ __device__ inline void ordered_select(const float *data, int n, unsigned thr, in
       const int rank = eq_before + __builtin_popcountll(eb & lanes_below(lane));
       const bool sel = g || (e && rank < take_eq);
       const unsigned long long sb = __builtin_amdgcn_ballot_w64(sel);
-      if (sel) out[pos + __builtin_popcountll(sb & lanes_below(lane))] = i;
+      if (sel) out[pos + __builtin_popcountll(sb & lanes_below(lane))] = name_of(i);
       pos += __builtin_popcountll(sb);
       eq_before += __builtin_popcountll(eb);
     }
@@ -744,15 +746,186 @@ __device__ inline int vs_merge_runs(const int32_t *offs, int k, int N, int2 *run
   return run_base;
 }
 
+// ---------------------------------------------------------------------------
+// Prefilter of the line-score top-k (Alg. 2: top-k of the column sums and of the
+// diagonal sums).  One workgroup streaming a 4 MiB row six times is bound by
+// latency, so the long rows are cut down first by many workgroups:
+//   vs_gmax_kernel    maximum of every group of G consecutive scores (G a power of two with
+//                     N / G >= 4 k);
+//   vs_bound_kernel   the k-th largest group maximum: k different scores reach it, so it is a
+//                     lower bound of the k-th largest score, and every score of the top-k set
+//                     (ties included) reaches it too;
+//   vs_filter_kernel  the scores that reach the bound, with their positions, compacted slice by
+//                     slice (in position order inside a slice; slices take their room from a
+//                     counter in arrival order and record where they put their part);
+//   vs_select_kernel  puts the parts in slice order and runs the exact selection on the
+//                     candidates (about 0.3 N / G of them) instead of the row.
+// If the candidates do not fit their buffer (plateaus of equal scores) or no G in 4 .. 64
+// satisfies N / G >= 4 k, vs_select_kernel selects from the whole row as before.  The result is
+// the same in both cases: exact top-k, equal scores to the lower position.
+// ---------------------------------------------------------------------------
+constexpr int VS_SLICE = 16384;                     // scores per workgroup of the filter
+struct VsSelState {                                 // per (head slot, which), in the workspace
+  unsigned bound;                                   // order key of the lower bound
+  int count;                                        // candidates taken so far (room counter)
+  int overflow;                                     // some slice found no room
+  int log_g;                                        // log2 G, or -1: no prefilter for this row
+};
+
+__device__ inline float key_to_float(unsigned key) {
+  return __uint_as_float((key & 0x80000000u) ? key ^ 0x80000000u : ~key);
+}
+
+// largest G = 2^g, 2 <= g <= 6, with N / G >= 4 k; -1 if there is none
+inline int vs_log_group(int N, int k) {
+  for (int g = 6; g >= 2; --g)
+    if ((int64_t)(N >> g) >= 4 * (int64_t)k) return g;
+  return -1;
+}
+
+// grid (ceil(N / 4096), heads, 2), 256 threads: thread t of a workgroup holds the scores
+// 4 (256 j + t) .. + 3 of its 4096; a group of G scores is G / 4 neighbouring lanes.
+__global__ __launch_bounds__(256) void vs_gmax_kernel(int N, int log_gv, int log_gs, const float *colsum,
+                                                      const float *diagsum, float *gmax_v, float *gmax_s) {
+  const int slot = blockIdx.y, which = blockIdx.z;
+  const int log_g = which == 0 ? log_gv : log_gs;
+  if (log_g < 0) return;
+  const float *data = (which == 0 ? colsum : diagsum) + (int64_t)slot * N;
+  float *gm = (which == 0 ? gmax_v : gmax_s) + (int64_t)slot * (N >> 2);
+  const int lanes = 1 << (log_g - 2);               // lanes per group
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int i = blockIdx.x * 4096 + (j * 256 + threadIdx.x) * 4;
+    unsigned m = 0u;                                 // below every key
+    if (i < N) {
+      const float4 a = *reinterpret_cast<const float4 *>(data + i);
+      m = max(max(order_key(a.x), order_key(a.y)), max(order_key(a.z), order_key(a.w)));
+    }
+    for (int off = 1; off < lanes; off <<= 1) m = max(m, (unsigned)__shfl_xor((int)m, off));
+    if (i < N && (threadIdx.x & (lanes - 1)) == 0) gm[i >> log_g] = key_to_float(m);
+  }
+}
+
+// grid (heads, 2), 1024 threads
+__global__ __launch_bounds__(1024) void vs_bound_kernel(int N, int nv, int ns, int log_gv, int log_gs,
+                                                        const float *gmax_v, const float *gmax_s,
+                                                        VsSelState *state) {
+  __shared__ int hist[256];
+  __shared__ int sh[16];
+  const int slot = blockIdx.x, which = blockIdx.y;
+  const int log_g = which == 0 ? log_gv : log_gs;
+  VsSelState *st = state + slot * 2 + which;
+  unsigned thr = 0u;
+  if (log_g >= 0) {
+    const float *gm = (which == 0 ? gmax_v : gmax_s) + (int64_t)slot * (N >> 2);
+    const int n_g = N >> log_g, k = min(which == 0 ? nv : ns, N);
+    int take_eq;
+    if ((n_g & 3) == 0) radix_select<1024, true>(gm, n_g, k, &thr, &take_eq, hist, sh);
+    else radix_select<1024, false>(gm, n_g, k, &thr, &take_eq, hist, sh);
+  }
+  if (threadIdx.x == 0) {
+    st->bound = thr;
+    st->count = 0;
+    st->overflow = 0;
+    st->log_g = log_g;
+  }
+}
+
+// grid (ceil(N / VS_SLICE), heads, 2), 256 threads.  Wave w of a workgroup owns the scores
+// 4096 w .. 4096 w + 4095 of the slice, 256 at a time (lane L: 4 L .. 4 L + 3), held in registers.
+__global__ __launch_bounds__(256) void vs_filter_kernel(int N, int cap, int n_slices, const float *colsum,
+                                                        const float *diagsum, VsSelState *state,
+                                                        float *cand_val, int32_t *cand_idx, int2 *seg) {
+  __shared__ int sh[8];
+  const int sl = blockIdx.x, slot = blockIdx.y, which = blockIdx.z;
+  VsSelState *st = state + slot * 2 + which;
+  int2 *myseg = seg + ((int64_t)(slot * 2 + which)) * n_slices + sl;
+  if (st->log_g < 0) return;
+  const unsigned bound = st->bound;
+  const float *data = (which == 0 ? colsum : diagsum) + (int64_t)slot * N;
+  float *cv = cand_val + (int64_t)(slot * 2 + which) * cap;
+  int32_t *ci = cand_idx + (int64_t)(slot * 2 + which) * cap;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int w0 = sl * VS_SLICE + wave * 4096;
+  float4 v[16];
+  int mine = 0;
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const int i = w0 + j * 256 + 4 * lane;
+    v[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i < N) {                                     // N is a multiple of 4
+      v[j] = *reinterpret_cast<const float4 *>(data + i);
+      mine += (order_key(v[j].x) >= bound) + (order_key(v[j].y) >= bound) + (order_key(v[j].z) >= bound) +
+              (order_key(v[j].w) >= bound);
+    }
+  }
+  // candidates of the waves before this one, and of the slice
+  int wsum = mine;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) wsum += __shfl_xor(wsum, off);
+  if (lane == 0) sh[wave] = wsum;
+  __syncthreads();
+  const int total = sh[0] + sh[1] + sh[2] + sh[3];
+  if (tid == 0) {
+    int base = 0;
+    if (total > 0) {
+      base = atomicAdd(&st->count, total);
+      if (base + total > cap) {
+        atomicExch(&st->overflow, 1);
+        base = -1;
+      }
+    }
+    sh[4] = base;
+    *myseg = make_int2(base, total);
+  }
+  __syncthreads();
+  const int base = sh[4];
+  if (total == 0 || base < 0) return;
+  int pos = base;
+  for (int w = 0; w < wave; ++w) pos += sh[w];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) {
+    const int i = w0 + j * 256 + 4 * lane;
+    const float e[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+    bool take[4];
+    int n_take = 0;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      take[c] = i < N && order_key(e[c]) >= bound;
+      n_take += take[c];
+    }
+    if (__builtin_amdgcn_ballot_w64(n_take > 0) == 0) continue;      // wave-uniform
+    int scan = n_take;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int o = __shfl_up(scan, off);
+      if (lane >= off) scan += o;
+    }
+    int p = pos + scan - n_take;
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+      if (take[c]) {
+        cv[p] = e[c];
+        ci[p] = i + c;
+        ++p;
+      }
+    pos += __shfl(scan, 63);
+  }
+}
+
 // Top-k + "sparseformat".  blockIdx.y = 0: verticals from the column sums;
 // blockIdx.y = 1: slashes from the diagonal sums, their runs and the run bitmap.
 __global__ __launch_bounds__(1024) void vs_select_kernel(int N, int nv, int ns, const float *colsum,
                                                          const float *diagsum, int32_t *v_idx,
                                                          int32_t *s_idx, int32_t *cover,
                                                          uint32_t *cover_bits, int32_t *counts,
-                                                         int cover_words) {
+                                                         int cover_words, int cap, int n_slices,
+                                                         const VsSelState *state, const float *cand_val,
+                                                         const int32_t *cand_idx, const int2 *seg,
+                                                         float *list_val, int32_t *list_idx) {
   __shared__ int hist[256];
   __shared__ int sh[40];
+  __shared__ int seg_pos[256];
   const int slot = blockIdx.x, which = blockIdx.y, tid = threadIdx.x;
   const float *data = (which == 0 ? colsum : diagsum) + (int64_t)slot * N;
   const int kcap = which == 0 ? nv : ns;
@@ -760,8 +933,40 @@ __global__ __launch_bounds__(1024) void vs_select_kernel(int N, int nv, int ns, 
   int32_t *out = which == 0 ? v_idx + (int64_t)slot * nv : s_idx + (int64_t)slot * ns;
   unsigned thr;
   int take_eq;
-  radix_select<1024, true>(data, N, k, &thr, &take_eq, hist, sh);      // N % 64 == 0, rows 256-byte aligned
-  ordered_select<1024, true>(data, N, thr, take_eq, out, sh + 8);
+  const VsSelState st = state[slot * 2 + which];
+  // the prefilter's candidates are complete (every slice found room) and in use for this row
+  const bool filtered = st.log_g >= 0 && st.overflow == 0 && st.count >= k && st.count <= cap && n_slices <= 256;
+  if (filtered) {
+    // the slices' parts, in slice order, into one list (position order)
+    const int2 *sg = seg + (int64_t)(slot * 2 + which) * n_slices;
+    if (tid == 0) {
+      int p = 0;
+      for (int i = 0; i < n_slices; ++i) {
+        seg_pos[i] = p;
+        p += sg[i].y;
+      }
+    }
+    __syncthreads();
+    const float *cv = cand_val + (int64_t)(slot * 2 + which) * cap;
+    const int32_t *ci = cand_idx + (int64_t)(slot * 2 + which) * cap;
+    float *lv = list_val + (int64_t)(slot * 2 + which) * cap;
+    int32_t *li = list_idx + (int64_t)(slot * 2 + which) * cap;
+    const int wave = tid >> 6, lane = tid & 63;
+    for (int i = wave; i < n_slices; i += 16) {
+      const int2 g = sg[i];
+      for (int e = lane; e < g.y; e += 64) {
+        lv[seg_pos[i] + e] = cv[g.x + e];
+        li[seg_pos[i] + e] = ci[g.x + e];
+      }
+    }
+    __threadfence_block();
+    __syncthreads();
+    radix_select<1024, false>(lv, st.count, k, &thr, &take_eq, hist, sh);
+    ordered_select<1024, false>(lv, st.count, thr, take_eq, out, sh + 8, li);
+  } else {
+    radix_select<1024, true>(data, N, k, &thr, &take_eq, hist, sh);      // N % 64 == 0, rows 256-byte aligned
+    ordered_select<1024, true>(data, N, thr, take_eq, out, sh + 8);
+  }
   for (int i = k + tid; i < kcap; i += 1024) out[i] = 0;
   if (which == 0) {
     if (tid == 0) counts[slot * 4 + 0] = k;
@@ -1053,11 +1258,18 @@ static inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
 static int vs_chunks(int N) { return (N + VS_CHUNK - 1) / VS_CHUNK; }
 
+static int vs_slices(int N) { return (N + VS_SLICE - 1) / VS_SLICE; }
+static int vs_cand_cap(int N) { return N / 4 > 1024 ? N / 4 : 1024; }        // candidates per (head, which)
+
 size_t vs_index_ws_bytes(int N, int n_heads) {
   size_t b = 0;
   b += 2 * align256((size_t)n_heads * N * sizeof(float));                     // colsum, diagsum
   b += align256((size_t)n_heads * vs_chunks(N) * 128 * sizeof(float));        // per-chunk (max, sum)
   b += align256((size_t)n_heads * 128 * sizeof(float));                       // final (max, 1/sum)
+  b += 2 * align256((size_t)n_heads * (N / 4) * sizeof(float));               // group maxima (G >= 4)
+  b += 4 * align256((size_t)n_heads * 2 * vs_cand_cap(N) * sizeof(float));    // candidates: parts and list, value and position
+  b += align256((size_t)n_heads * 2 * vs_slices(N) * sizeof(int2));           // where every slice put its part
+  b += align256((size_t)n_heads * 2 * sizeof(VsSelState));
   return b;
 }
 
@@ -1069,7 +1281,17 @@ hipError_t launch_build_vs(const QKV &x, const HeadList &hl, int last_q, int nv,
   float *colsum = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * N * sizeof(float));
   float *diagsum = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * N * sizeof(float));
   float *ml_part = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * nc * 128 * sizeof(float));
-  float *ml_fin = reinterpret_cast<float *>(p);
+  float *ml_fin = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * 128 * sizeof(float));
+  const int cap = vs_cand_cap(N), n_slices = vs_slices(N);
+  float *gmax_v = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * (N / 4) * sizeof(float));
+  float *gmax_s = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * (N / 4) * sizeof(float));
+  const size_t cand_bytes = align256((size_t)hl.n * 2 * cap * sizeof(float));
+  float *cand_val = reinterpret_cast<float *>(p); p += cand_bytes;
+  int32_t *cand_idx = reinterpret_cast<int32_t *>(p); p += cand_bytes;
+  float *list_val = reinterpret_cast<float *>(p); p += cand_bytes;
+  int32_t *list_idx = reinterpret_cast<int32_t *>(p); p += cand_bytes;
+  int2 *seg = reinterpret_cast<int2 *>(p); p += align256((size_t)hl.n * 2 * n_slices * sizeof(int2));
+  VsSelState *state = reinterpret_cast<VsSelState *>(p);
   // the listed heads grouped by K/V head, in order of first appearance, at most four per group
   VsGroups vg;
   memset(&vg, 0, sizeof(vg));
@@ -1093,8 +1315,21 @@ hipError_t launch_build_vs(const QKV &x, const HeadList &hl, int last_q, int nv,
   hipLaunchKernelGGL(vs_combine_kernel, dim3(hl.n), dim3(1024), 0, st, nc, (const float *)ml_part, ml_fin);
   hipLaunchKernelGGL(vs_score_kernel<2>, grid, dim3(256), lds2, st, x, hl, vg, last_q, nc, (float *)nullptr,
                      (const float *)ml_fin, colsum, diagsum);
+  // top-k of the line scores: prefilter by many workgroups, exact selection on what is left
+  const int kv_ = nv < N ? nv : N, ks_ = ns < N ? ns : N;
+  const int log_gv = vs_log_group(N, kv_), log_gs = vs_log_group(N, ks_);
+  if (log_gv >= 0 || log_gs >= 0)
+    hipLaunchKernelGGL(vs_gmax_kernel, dim3((N + 4095) / 4096, hl.n, 2), dim3(256), 0, st, N, log_gv, log_gs,
+                       (const float *)colsum, (const float *)diagsum, gmax_v, gmax_s);
+  hipLaunchKernelGGL(vs_bound_kernel, dim3(hl.n, 2), dim3(1024), 0, st, N, nv, ns, log_gv, log_gs,
+                     (const float *)gmax_v, (const float *)gmax_s, state);
+  if (log_gv >= 0 || log_gs >= 0)
+    hipLaunchKernelGGL(vs_filter_kernel, dim3(n_slices, hl.n, 2), dim3(256), 0, st, N, cap, n_slices,
+                       (const float *)colsum, (const float *)diagsum, state, cand_val, cand_idx, seg);
   hipLaunchKernelGGL(vs_select_kernel, dim3(hl.n, 2), dim3(1024), 0, st, N, nv, ns, (const float *)colsum,
-                     (const float *)diagsum, v_idx, s_idx, cover, cover_bits, counts, cover_words);
+                     (const float *)diagsum, v_idx, s_idx, cover, cover_bits, counts, cover_words, cap, n_slices,
+                     (const VsSelState *)state, (const float *)cand_val, (const int32_t *)cand_idx,
+                     (const int2 *)seg, list_val, list_idx);
   return hipGetLastError();
 }
 

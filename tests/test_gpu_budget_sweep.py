@@ -47,6 +47,7 @@ def test_budget_setting_matches_oracle(B, layer, label, nv, ns):
     B.minf_vs_attn(x.q, x.k, x.v, o, heads, idx)
     torch.cuda.synchronize()
     tiles_gpu = C.vs_index_tiles(idx, N)
+    steps_gpu = C.vs_index_steps(idx, N)
     NB = N // 64
     blocks = sorted({0, 1, 2, NB // 2, NB - 2, NB - 1, *np.random.default_rng(nv + ns).integers(0, NB, 6).tolist()})
     for r, h in enumerate(heads):
@@ -59,6 +60,42 @@ def test_budget_setting_matches_oracle(B, layer, label, nv, ns):
         check_topk(Vg, col, nv)
         check_topk(Sg, diag, ns)
         assert np.array_equal(tiles_gpu[r], O.tiles_vs(N, Vg, Sg)), f"{label}: tile count of head {h}"
+        assert np.array_equal(steps_gpu[r], O.tiles_vs(N, Vg, Sg, 64, 32)), f"{label}: executed steps of head {h}"
         for b in blocks:
             want = O.vs_attention(Qh, Kh, Vh, Vg, Sg, 64 * b, 64 * b + 64)
             assert_close_rows(o[h, 64 * b:64 * b + 64], want, f"{label} head {h} block {b}")
+
+
+@pytest.mark.parametrize("nv,ns", [(30, 64), (100, 300), (1000, 6096)])
+def test_output_distance_from_dense_matches_the_oracle(B, layer, nv, ns):
+    """The criterion of the head-pattern search (Alg. 1): relative L2 distance of the sparse output
+    from the dense causal one.  bench.py reports it from the library's two outputs; here the same
+    reduction over sampled query blocks is compared with the distance of the oracle's two outputs
+    (sparse with the GPU's own index) on the same blocks."""
+    import bench
+    x, heads = layer, [0, 1]
+    idx = B.alloc_vs_index(len(heads), nv, ns, N)
+    ws = torch.empty(B.minf_vs_index_workspace_bytes(x.q, x.k, len(heads), 64), dtype=torch.uint8, device="cuda")
+    o_sparse, o_dense = torch.empty_like(x.q), torch.empty_like(x.q)
+    B.minf_build_vs_index(x.q, x.k, heads, 64, nv, ns, idx, ws)
+    B.minf_vs_attn(x.q, x.k, x.v, o_sparse, heads, idx)
+    B.minf_dense_attn(x.q, x.k, x.v, o_dense, heads)
+    torch.cuda.synchronize()
+    NB = N // 64
+    blocks = sorted({1, NB // 3, NB // 2, NB - 1, *np.random.default_rng(ns).integers(0, NB, 8).tolist()})
+    rows = torch.cat([torch.arange(64 * b, 64 * b + 64) for b in blocks]).cuda()
+    got = bench.output_distance(o_sparse[:, rows], o_dense[:, rows], heads)
+    num = den = 0.0
+    for r, h in enumerate(heads):
+        Qh, Kh, Vh = x.head_f64(h)
+        c = idx.counts[r].cpu().numpy()
+        Vg, Sg = idx.v_idx[r, :c[0]].cpu().numpy(), idx.s_idx[r, :c[1]].cpu().numpy()
+        for b in blocks:
+            sp = O.vs_attention(Qh, Kh, Vh, Vg, Sg, 64 * b, 64 * b + 64)
+            de = O.dense_attention(Qh, Kh, Vh, 64 * b, 64 * b + 64)
+            num += float(np.sum((sp - de) ** 2))
+            den += float(np.sum(de ** 2))
+    want = float(np.sqrt(num / den))
+    # both outputs carry bf16 rounding (relative 2^-9 each); a distance of a few percent or more
+    # is reproduced to a few percent of itself
+    assert abs(got - want) <= 0.03 * want + 2e-3, (got, want)
