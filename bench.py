@@ -375,13 +375,30 @@ def cpu_baseline(layer, budget_s=20.0):
 def device_peak():
     """The bf16 dense MFMA peak derived from what the device reports: compute units x 4 SIMDs x
     1024 FLOP per SIMD and clock (v_mfma_f32_32x32x16_bf16: 32768 FLOP in 8 passes of 4 clocks)
-    x the maximum engine clock.  roofline.frac divides by the published 2.5 PFLOP/s."""
+    x the maximum engine clock (read from rocminfo's GPU agent).  roofline.frac divides by the
+    published 2.5 PFLOP/s."""
+    import re
+    import subprocess
     p = torch.cuda.get_device_properties(0)
-    cus, mhz = int(p.multi_processor_count), float(p.clock_rate) / 1e3
-    return {"device": p.name, "compute_units": cus, "max_engine_clock_mhz": round(mhz, 1),
-            "flop_per_clock_per_cu": 4096,
-            "derived_bf16_tflops": round(cus * 4096 * mhz * 1e6 / 1e12, 1),
-            "published_bf16_tflops": PEAK_BF16_TFLOPS}
+    cus, mhz = int(p.multi_processor_count), None
+    try:
+        txt = subprocess.run(["rocminfo"], capture_output=True, text=True, timeout=30).stdout
+        for agent in txt.split("Agent ")[1:]:
+            if "gfx" in agent and re.search(r"Device Type:\s*GPU", agent):
+                m = re.search(r"Max Clock Freq\. \(MHz\):\s*(\d+)", agent)
+                c = re.search(r"Compute Unit:\s*(\d+)", agent)
+                if m:
+                    mhz = float(m.group(1))
+                if c:
+                    cus = int(c.group(1))
+                break
+    except Exception:
+        pass
+    out = {"device": p.name, "compute_units": cus, "max_engine_clock_mhz": mhz, "flop_per_clock_per_cu": 4096,
+           "published_bf16_tflops": PEAK_BF16_TFLOPS}
+    if mhz:
+        out["derived_bf16_tflops"] = round(cus * 4096 * mhz * 1e6 / 1e12, 1)
+    return out
 
 
 def roofline_of(rep, workload):

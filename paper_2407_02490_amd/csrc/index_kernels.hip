@@ -776,8 +776,10 @@ __device__ inline float key_to_float(unsigned key) {
   return __uint_as_float((key & 0x80000000u) ? key ^ 0x80000000u : ~key);
 }
 
-// largest G = 2^g, 2 <= g <= 6, with N / G >= 4 k; -1 if there is none
+// largest G = 2^g, 2 <= g <= 6, with N / G >= 4 k; -1 if there is none, or if the row is so short
+// that the three extra launches cost more than they save (below 128K scores)
 inline int vs_log_group(int N, int k) {
+  if (N < 131072) return -1;
   for (int g = 6; g >= 2; --g)
     if ((int64_t)(N >> g) >= 4 * (int64_t)k) return g;
   return -1;
@@ -933,7 +935,10 @@ __global__ __launch_bounds__(1024) void vs_select_kernel(int N, int nv, int ns, 
   int32_t *out = which == 0 ? v_idx + (int64_t)slot * nv : s_idx + (int64_t)slot * ns;
   unsigned thr;
   int take_eq;
-  const VsSelState st = state[slot * 2 + which];
+  // n_slices == 0: the launch ran no prefilter (the state was not written)
+  VsSelState st;
+  st.bound = 0u; st.count = 0; st.overflow = 1; st.log_g = -1;
+  if (n_slices > 0) st = state[slot * 2 + which];
   // the prefilter's candidates are complete (every slice found room) and in use for this row
   const bool filtered = st.log_g >= 0 && st.overflow == 0 && st.count >= k && st.count <= cap && n_slices <= 256;
   if (filtered) {
@@ -1321,14 +1326,16 @@ hipError_t launch_build_vs(const QKV &x, const HeadList &hl, int last_q, int nv,
   if (log_gv >= 0 || log_gs >= 0)
     hipLaunchKernelGGL(vs_gmax_kernel, dim3((N + 4095) / 4096, hl.n, 2), dim3(256), 0, st, N, log_gv, log_gs,
                        (const float *)colsum, (const float *)diagsum, gmax_v, gmax_s);
-  hipLaunchKernelGGL(vs_bound_kernel, dim3(hl.n, 2), dim3(1024), 0, st, N, nv, ns, log_gv, log_gs,
-                     (const float *)gmax_v, (const float *)gmax_s, state);
-  if (log_gv >= 0 || log_gs >= 0)
+  const bool prefilter = log_gv >= 0 || log_gs >= 0;
+  if (prefilter)
+    hipLaunchKernelGGL(vs_bound_kernel, dim3(hl.n, 2), dim3(1024), 0, st, N, nv, ns, log_gv, log_gs,
+                       (const float *)gmax_v, (const float *)gmax_s, state);
+  if (prefilter)
     hipLaunchKernelGGL(vs_filter_kernel, dim3(n_slices, hl.n, 2), dim3(256), 0, st, N, cap, n_slices,
                        (const float *)colsum, (const float *)diagsum, state, cand_val, cand_idx, seg);
   hipLaunchKernelGGL(vs_select_kernel, dim3(hl.n, 2), dim3(1024), 0, st, N, nv, ns, (const float *)colsum,
-                     (const float *)diagsum, v_idx, s_idx, cover, cover_bits, counts, cover_words, cap, n_slices,
-                     (const VsSelState *)state, (const float *)cand_val, (const int32_t *)cand_idx,
+                     (const float *)diagsum, v_idx, s_idx, cover, cover_bits, counts, cover_words, cap,
+                     prefilter ? n_slices : 0, (const VsSelState *)state, (const float *)cand_val, (const int32_t *)cand_idx,
                      (const int2 *)seg, list_val, list_idx);
   return hipGetLastError();
 }

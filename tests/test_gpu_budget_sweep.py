@@ -96,6 +96,7 @@ def test_output_distance_from_dense_matches_the_oracle(B, layer, nv, ns):
             num += float(np.sum((sp - de) ** 2))
             den += float(np.sum(de ** 2))
     want = float(np.sqrt(num / den))
-    # both outputs carry bf16 rounding (relative 2^-9 each); a distance of a few percent or more
-    # is reproduced to a few percent of itself
-    assert abs(got - want) <= 0.03 * want + 2e-3, (got, want)
+    # both library outputs carry bf16 rounding (relative 2^-9 each), which alone puts two equal
+    # results about 4e-3 apart; a distance of a few percent or more is reproduced to a few
+    # percent of itself
+    assert abs(got - want) <= 0.03 * want + 6e-3, (got, want)
