@@ -91,7 +91,7 @@ class Layer:
             self.vs_ws = u8(B.minf_vs_index_workspace_bytes(x.q, x.k, len(self.vs_heads), c["last_q"]))
         if self.bs_heads:
             self.bs_idx = B.alloc_bs_index(len(self.bs_heads), self.N, c["topk"])
-            self.bs_ws = u8(B.minf_bs_index_workspace_bytes(x.q, x.k, len(self.bs_heads)))
+            self.bs_ws = u8(B.minf_bs_index_workspace_bytes(x.q, x.k, len(self.bs_heads), c["topk"]))
         self.t = {k: Timer() for k in ("vs_index", "bs_index", "ashape_attn", "vs_attn", "bs_attn")}
 
     def step(self):

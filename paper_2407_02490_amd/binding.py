@@ -70,7 +70,7 @@ def lib():
     L.minf_vs_index_workspace_bytes.restype = sz
     L.minf_vs_index_workspace_bytes.argtypes = [pq, i32, i32]
     L.minf_bs_index_workspace_bytes.restype = sz
-    L.minf_bs_index_workspace_bytes.argtypes = [pq, i32]
+    L.minf_bs_index_workspace_bytes.argtypes = [pq, i32, i32]
     L.minf_build_vs_index.restype = ctypes.c_int
     L.minf_build_vs_index.argtypes = [pq, pi, i32, i32, i32, i32, i32, ctypes.POINTER(_VSIndex), vp, sz, vp]
     L.minf_build_vs_index_noalloc.restype = ctypes.c_int
@@ -228,9 +228,10 @@ def minf_vs_index_workspace_bytes(q, k, n_heads, last_q=64):
     return int(lib().minf_vs_index_workspace_bytes(ctypes.byref(x), n_heads, last_q))
 
 
-def minf_bs_index_workspace_bytes(q, k, n_heads):
+def minf_bs_index_workspace_bytes(q, k, n_heads, topk=None):
+    """topk=None: enough for any budget (the size of the unfused path)."""
     x = _qkv(q, k)
-    return int(lib().minf_bs_index_workspace_bytes(ctypes.byref(x), n_heads))
+    return int(lib().minf_bs_index_workspace_bytes(ctypes.byref(x), n_heads, 2 ** 31 - 1 if topk is None else topk))
 
 
 def minf_build_vs_index(q, k, heads, last_q, nv, ns, out, ws, block=BLOCK, scale=0.0, stream=None):

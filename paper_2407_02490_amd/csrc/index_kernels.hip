@@ -1010,7 +1010,9 @@ __global__ __launch_bounds__(1024) void vs_lines_kernel(int N, int nv, int ns, c
 // Block-Sparse: pooling, block logits, per-row top-k
 // ---------------------------------------------------------------------------
 // grid (NB, n_heads + n_kv): y < n_heads pools Q of head slot y, else K of kv[y - n_heads]
-__global__ __launch_bounds__(256) void bs_pool_kernel(QKV x, HeadList hl, KvMap km, float *qpool, float *kpool) {
+// (the pooled K vectors of a K/V head are NBp >= NB rows apart: padded to whole 32-row tiles)
+__global__ __launch_bounds__(256) void bs_pool_kernel(QKV x, HeadList hl, KvMap km, float *qpool, float *kpool,
+                                                      int NBp) {
   __shared__ float red[16][132];
   const int b = blockIdx.x, y = blockIdx.y, NB = x.N / 64;
   const bf16_t *src;
@@ -1019,7 +1021,7 @@ __global__ __launch_bounds__(256) void bs_pool_kernel(QKV x, HeadList hl, KvMap 
   if (y < hl.n) {
     src = x.q + hl.h[y] * x.q_sh; st = x.q_st; dst = qpool + ((int64_t)y * NB + b) * 128;
   } else {
-    src = x.k + km.kv[y - hl.n] * x.k_sh; st = x.k_st; dst = kpool + ((int64_t)(y - hl.n) * NB + b) * 128;
+    src = x.k + km.kv[y - hl.n] * x.k_sh; st = x.k_st; dst = kpool + ((int64_t)(y - hl.n) * NBp + b) * 128;
   }
   const int tid = threadIdx.x, r = tid >> 4, c = tid & 15;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -1046,7 +1048,7 @@ __global__ __launch_bounds__(256) void bs_pool_kernel(QKV x, HeadList hl, KvMap 
 
 // Block logits of the lower triangle, one wave per 64 x 64 tile, fp32 MFMA
 // (v_mfma_f32_32x32x2_f32).  grid (tiles of the lower triangle, heads of the batch).
-__global__ __launch_bounds__(64) void bs_logits_kernel(int NB, int slot0, KvMap km, const float *qpool,
+__global__ __launch_bounds__(64) void bs_logits_kernel(int NB, int NBp, int slot0, KvMap km, const float *qpool,
                                                        const float *kpool, float *scores, float scale) {
   const int t = blockIdx.x, hb = blockIdx.y, slot = slot0 + hb;
   // t -> (ti, tj), tj <= ti
@@ -1056,7 +1058,7 @@ __global__ __launch_bounds__(64) void bs_logits_kernel(int NB, int slot0, KvMap 
   const int tj = t - ti * (ti + 1) / 2;
   const int lane = threadIdx.x, n = lane & 31, h = lane >> 5;
   const float *qp = qpool + (int64_t)slot * NB * 128;
-  const float *kp = kpool + (int64_t)km.slot_kv[slot] * NB * 128;
+  const float *kp = kpool + (int64_t)km.slot_kv[slot] * NBp * 128;
   f32x16 acc[2][2];
 #pragma unroll
   for (int a = 0; a < 2; ++a)
@@ -1220,6 +1222,347 @@ __global__ __launch_bounds__(256) void bs_select_kernel(int NB, int slot0, int t
   ordered_select<256, false>(row, n, thr, take_eq, out, sh + 8);
 }
 
+// ---------------------------------------------------------------------------
+// Block logits and per-row top-k in one kernel (Alg. 3): the NB x NB logits are never stored.
+// Workgroup = 128 query blocks of one head, 16 per wave, eight waves: two per SIMD, so that one
+// wave's selection work runs while the other's MFMAs occupy the matrix pipeline (a single wave
+// issues in order and gets no such overlap).  Per 32-key tile (pooled K vectors staged in LDS,
+// shared by the eight waves, double buffered) a wave forms its 32 x 16 logits transposed,
+// S^T = K_hat Q_hat^T with the 16 x 16 x 4 fp32 MFMA, so that the four lanes n, n + 16, n + 32,
+// n + 48 hold the logits of ONE query block n: the top-k state of a row is private to its four
+// lanes, and no atomics or cross-row traffic are needed.
+// Per row: a candidate list in LDS (order key of the logit + key block, at most BSF_CAP entries,
+// in key-block order) and a bar tau: a logit enters the list iff its key exceeds tau.  When a
+// list cannot take its share of a tile, its row finds by bisection a key T with at least k
+// entries >= T, drops what is below, keeps of the entries equal to T only the first it still
+// needs, and raises tau to T: k or more entries with a lower key block reach T, so a later logit
+// <= T cannot be among the k largest (ties go to the lower block).  After the last tile the same
+// step with the exact k-th largest key leaves exactly the k selected blocks, already ascending.
+// Needs topk <= BSF_MAX_TOPK and NB < 65536 (block ids are kept in 16 bits).
+// ---------------------------------------------------------------------------
+constexpr int BSF_ROWS = 128;                       // query blocks per workgroup
+constexpr int BSF_THREADS = 512;
+constexpr int BSF_CAP = 160;                        // candidates a row can hold
+constexpr int BSF_PITCH = 164;                      // entries between rows: a multiple of 4 (16-byte reads)
+                                                    // and an odd multiple of 4 (16 rows hit 64 different banks)
+constexpr int BSF_SLACK = 16;                       // the bisection of a running cut stops at k .. k + slack entries
+constexpr int BSF_MAX_TOPK = BSF_CAP - 32 - BSF_SLACK;   // 32: what one tile can add to a row
+constexpr int BSF_TILE_BYTES = 32 * 512;            // 32 pooled vectors of 128 floats
+constexpr size_t BSF_LDS = 2 * BSF_TILE_BYTES + (size_t)BSF_ROWS * BSF_PITCH * (4 + 2);
+
+// the lists are addressed as LDS (not through generic pointers) also inside the functions below
+typedef __attribute__((address_space(3))) unsigned lds_u32;
+typedef __attribute__((address_space(3))) unsigned short lds_u16;
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+typedef __attribute__((address_space(3))) u32x2 lds_u32x2;
+
+constexpr int BSF_GROUPS = BSF_CAP / 16;            // 4-entry groups of a list that one of the row's four lanes holds
+
+// sum over the four lanes of a row
+__device__ __forceinline__ int bsf_row_sum(int v) {
+  v += __shfl_xor(v, 16);
+  return v + __shfl_xor(v, 32);
+}
+
+// Serial form of the cut below, for a row whose entries equal to T are more than it may keep: of
+// those the first `quota` in list order (the lowest key blocks) stay.  The row's first lane walks
+// the list, 32 entries at a time through registers: the reads of a chunk are issued together and
+// the writes land at or below positions already read.  Returns the new count (valid in that lane).
+__device__ inline int bsf_cut_serial(lds_u32 *keys, lds_u16 *idx, int cnt, unsigned T, int quota, int hq) {
+  int out = 0;
+  if (hq == 0) {
+    for (int c0 = 0; c0 < cnt; c0 += 32) {
+      unsigned kv[32], bv[32];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const u32x4 e = *reinterpret_cast<const lds_u32x4 *>(keys + c0 + 4 * j);
+        const u32x2 b = *reinterpret_cast<const lds_u32x2 *>(idx + c0 + 4 * j);
+        kv[4 * j] = e.x; kv[4 * j + 1] = e.y; kv[4 * j + 2] = e.z; kv[4 * j + 3] = e.w;
+        bv[4 * j] = b.x & 0xffffu; bv[4 * j + 1] = b.x >> 16; bv[4 * j + 2] = b.y & 0xffffu; bv[4 * j + 3] = b.y >> 16;
+      }
+#pragma unroll
+      for (int i = 0; i < 32; ++i) {
+        const unsigned v = kv[i];
+        const bool live = c0 + i < cnt;                      // what lies behind the list is stale
+        bool keep = v > T;
+        if (v == T && quota > 0 && live) { keep = true; --quota; }
+        if (keep && live) { keys[out] = v; idx[out] = (unsigned short)bv[i]; ++out; }
+      }
+    }
+  }
+  return out;
+}
+
+// Cut of one row's list (the four lanes of the row call it with the same arguments; every lane of
+// the wave calls it).  tau: the row's bar, which every entry's key reaches.  A row with more than
+// `limit` entries (limit = k when exact, else k + slack) finds a key T with k .. limit entries
+// >= T, keeps those and raises its bar to T; the others keep what they have.  Returns the new
+// count and bar.
+// The lane of quarter hq holds the list's 4-entry groups hq, hq + 4, ... in registers for the
+// whole step (the bisection then costs no memory access), and the four lanes write the kept
+// entries back at the same time, after all reads: the position of a group is the number of kept
+// entries in the groups before it, over the four lanes.  Dropped entries go to the slot behind
+// the list's capacity.
+// (A function of its own, not inlined: its registers would otherwise be live through the
+// caller's inner loop.)
+struct BsfCut { int cnt; unsigned tau; };                   // returned in registers: nothing of the caller's lives in memory
+__device__ __noinline__ BsfCut bsf_compact(lds_u32 *keys, lds_u16 *idx, int cnt, int k, bool exact, int hq,
+                                           unsigned tau) {
+  unsigned kv[BSF_GROUPS][4];
+  u32x2 bv[BSF_GROUPS];
+  unsigned hi = 0u;
+#pragma unroll
+  for (int g = 0; g < BSF_GROUPS; ++g) {
+    const int base = 16 * g + 4 * hq;                          // < BSF_CAP <= BSF_PITCH - 4: inside the row
+    const u32x4 e = *reinterpret_cast<const lds_u32x4 *>(keys + base);
+    bv[g] = *reinterpret_cast<const lds_u32x2 *>(idx + base);
+    const unsigned v[4] = {e.x, e.y, e.z, e.w};
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      kv[g][c] = base + c < cnt ? v[c] : 0u;                   // live keys are >= 1
+      hi = max(hi, kv[g][c]);
+    }
+  }
+  hi = max(hi, (unsigned)__shfl_xor((int)hi, 16));
+  hi = max(hi, (unsigned)__shfl_xor((int)hi, 32));
+  auto count_ge = [&](unsigned v) {
+    int c = 0;
+#pragma unroll
+    for (int g = 0; g < BSF_GROUPS; ++g)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) c += kv[g][j] >= v;
+    return bsf_row_sum(c);
+  };
+  const int limit = exact ? k : k + min(BSF_SLACK, (BSF_CAP - 32 - k) / 2);
+  const bool cut = cnt > limit;
+  // invariant: at least k entries are >= lo (at the start all of them: an entry exceeded the bar of
+  // its time, and a cut keeps what reaches the new bar); fewer than k are > hi
+  unsigned lo = tau;
+  bool act = cut && lo < hi;
+  while (__builtin_amdgcn_ballot_w64(act)) {
+    const unsigned mid = lo + ((hi - lo + 1u) >> 1);           // lo < mid <= hi
+    const int c = count_ge(mid);
+    if (act) {
+      if (c >= k) {
+        lo = mid;
+        if (c <= limit) act = false;
+      } else {
+        hi = mid - 1u;
+      }
+      if (lo >= hi) act = false;
+    }
+  }
+  if (!cut) return BsfCut{cnt, tau};                           // nothing moves: list and bar stay
+  const unsigned T = lo;
+  const int reach = count_ge(T);                               // >= k
+  const bool ties = reach > limit;                             // too many entries equal to T: serial cut
+  int serial_cnt = 0;
+  if (__builtin_amdgcn_ballot_w64(ties)) {
+    if (ties) {
+      const int above = T == 0xffffffffu ? 0 : count_ge(T + 1u);
+      serial_cnt = bsf_cut_serial(keys, idx, cnt, T, k - above, hq);
+    }
+    serial_cnt = __shfl(serial_cnt, threadIdx.x & 15);         // from the row's first lane
+  }
+  // kept entries per group: prefix over this lane's groups, exclusive and inclusive, one byte each
+  unsigned excl[3] = {0u, 0u, 0u}, incl[3] = {0u, 0u, 0u};
+  {
+    int run = 0;
+#pragma unroll
+    for (int g = 0; g < BSF_GROUPS; ++g) {
+      excl[g >> 2] |= (unsigned)run << (8 * (g & 3));
+#pragma unroll
+      for (int j = 0; j < 4; ++j) run += kv[g][j] >= T;
+      incl[g >> 2] |= (unsigned)run << (8 * (g & 3));
+    }
+  }
+  // list position of this lane's group g = kept entries of all groups before it: of a lane with a
+  // lower quarter the groups 0 .. g, of one with a higher quarter the groups 0 .. g-1.  Each lane
+  // sends each of the other three what that one needs; sums stay below 256 per byte.
+  unsigned at_pk[3] = {excl[0], excl[1], excl[2]};
+#pragma unroll
+  for (int x = 1; x < 4; ++x) {
+    const bool lower = hq < (hq ^ x);                          // this lane comes before its partner
+#pragma unroll
+    for (int w = 0; w < 3; ++w) {
+      const unsigned send = lower ? incl[w] : excl[w];
+      const int lane_x = 16 * x;
+      at_pk[w] += (unsigned)__shfl_xor((int)send, lane_x);
+    }
+  }
+#pragma unroll
+  for (int g = 0; g < BSF_GROUPS; ++g) {
+    int pos = (at_pk[g >> 2] >> (8 * (g & 3))) & 255u;
+    const unsigned b[4] = {bv[g].x & 0xffffu, bv[g].x >> 16, bv[g].y & 0xffffu, bv[g].y >> 16};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const bool keep = kv[g][j] >= T && !ties;
+      const int at = keep ? pos : BSF_CAP + hq;                // behind the capacity: slots nobody reads, one per lane
+      keys[at] = kv[g][j];
+      idx[at] = (unsigned short)b[j];
+      pos += keep;
+    }
+  }
+  return BsfCut{ties ? serial_cnt : reach, T};
+}
+
+// The float whose order key is the bar (below / above every real logit outside the keys of real
+// floats): a logit's key exceeds the bar iff the logit exceeds this value (the two zeros count
+// as equal here).
+__device__ inline float bsf_bar_value(unsigned tau) {
+  if (tau <= 0x007fffffu) return -__builtin_inff();
+  if (tau >= 0xff800000u) return __builtin_inff();
+  return __uint_as_float((tau & 0x80000000u) ? (tau & 0x7fffffffu) : ~tau);
+}
+
+__device__ __forceinline__ void bsf_load_q(const float *qp, float (&q)[32]) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const float4 v = *reinterpret_cast<const float4 *>(qp + 4 * j);
+    q[4 * j] = v.x; q[4 * j + 1] = v.y; q[4 * j + 2] = v.z; q[4 * j + 3] = v.w;
+  }
+}
+
+__global__ __launch_bounds__(BSF_THREADS) void bs_topk_kernel(int NB, int NBp, int topk, KvMap km, const float *qpool,
+                                                              const float *kpool, int32_t *blk_idx, int32_t *blk_cnt) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  unsigned *ckey = reinterpret_cast<unsigned *>(lds + 2 * BSF_TILE_BYTES);
+  unsigned short *cidx = reinterpret_cast<unsigned short *>(ckey + BSF_ROWS * BSF_PITCH);
+  const int slot = blockIdx.x;
+  const int R0 = (gridDim.y - 1 - blockIdx.y) * BSF_ROWS;    // the longest rows of every head first
+  const int tid = threadIdx.x, lane = tid & 63, n = lane & 15, hq = lane >> 4;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int row = R0 + 16 * wave + n;                        // query block of these four lanes
+  const bool row_ok = row < NB;
+  const int k = min(topk, row + 1);
+  lds_u32 *keys = (lds_u32 *)ckey + (16 * wave + n) * BSF_PITCH;    // this row's list
+  lds_u16 *idx = (lds_u16 *)cidx + (16 * wave + n) * BSF_PITCH;
+  int cnt = 0;
+  unsigned tau = row_ok ? 0u : 0xffffffffu;                  // every entry's key reaches it; a logit enters iff its key
+  float bar = bsf_bar_value(tau);                            // exceeds it.  Rows past the end take nothing.
+
+  // B operand: Q_hat[row][32 hq + j], j = 0 .. 31 (the contraction index of the lane of quarter hq in
+  // MFMA step j is 32 hq + j, for both operands).  Read again after every cut of the lists: 32
+  // values that need not live through that call.
+  const float *qp = qpool + ((int64_t)slot * NB + min(row, NB - 1)) * 128 + 32 * hq;
+  float q[32];
+  bsf_load_q(qp, q);
+  const float *kp = kpool + (int64_t)km.slot_kv[slot] * NBp * 128;
+  const int last_row = min(R0 + BSF_ROWS, NB) - 1;           // last query block of the workgroup
+  const int n_tiles = last_row / 32 + 1;                     // key tiles that hold a key <= last_row
+  const int wave_first = R0 + 16 * wave;
+  const int t_last = wave_first < NB ? min(wave_first + 15, NB - 1) / 32 : -1;   // last tile with a causal key for this wave
+
+  // Tile t = pooled K rows 32 t .. 32 t + 31 (kpool is padded to whole tiles), 512 bytes each, in
+  // LDS with the 16-byte chunk c of row m at chunk position c ^ (m % 16): the 16 lanes that read
+  // one chunk column of 16 rows hit all 64 banks.  One load instruction fills two rows; this wave
+  // issues two of the sixteen.
+  auto fetch = [&](int t) {
+    const float *ubase = kp + (int64_t)(32 * t) * 128;
+    const unsigned base = lds_addr_of(lds + (t & 1) * BSF_TILE_BYTES);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int b = 2 * wave + i, r = 2 * b + (lane >> 5), p = lane & 31;
+      const unsigned voff = (unsigned)r * 512u + (unsigned)((p ^ (r & 15)) << 4);
+      dma16_su(ubase, voff, base + b * 1024);
+    }
+  };
+
+  // Selection of one tile's logits sc[e], e = 4 b + r: key block kb + 16 b + 4 hq + r against this row.
+  auto select = [&](const float (&sc)[8], int kb) {
+    unsigned takes = 0u;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) takes |= sc[e] > bar ? 1u << e : 0u;
+    if (kb + 31 > wave_first) {                              // only a tile on the diagonal holds keys past a row
+      const int rel = row - kb - 4 * hq;                     // entry e is causal iff 16 b + r <= rel
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (16 * (e >> 2) + (e & 3) > rel) takes &= ~(1u << e);
+    }
+    if (__builtin_amdgcn_ballot_w64(takes != 0u) == 0) return;
+    // A list that cannot take its share of this tile: every row of the wave that holds more than
+    // it must is cut down with it (the rows then fill up together: one cut where the wave would
+    // pay for sixteen), and what the raised bars exclude leaves the tile's share.  A cut leaves a
+    // row at most BSF_CAP - 32 entries, so its share fits.
+    if (__builtin_amdgcn_ballot_w64(cnt + bsf_row_sum(__builtin_popcount(takes)) > BSF_CAP)) {
+      const BsfCut c = bsf_compact(keys, idx, cnt, k, false, hq, tau);
+      cnt = c.cnt; tau = c.tau;
+      asm volatile("" ::: "memory");
+      bsf_load_q(qp, q);
+      bar = bsf_bar_value(tau);
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (!(sc[e] > bar)) takes &= ~(1u << e);
+    }
+    // list order = key-block order: within a 16-key block the four lanes of the row follow each
+    // other with four keys each.  Counts of the two blocks, one byte each, from all four lanes.
+    const unsigned mine = (unsigned)__builtin_popcount(takes & 15u) | (unsigned)__builtin_popcount(takes >> 4) << 8;
+    const unsigned p1 = (unsigned)__shfl_xor((int)mine, 16), p2 = (unsigned)__shfl_xor((int)mine, 32);
+    const unsigned p3 = (unsigned)__shfl_xor((int)p1, 32);    // of the lanes hq ^ 1, hq ^ 2, hq ^ 3
+    const unsigned all = mine + p1 + p2 + p3;
+    const unsigned before = ((hq ^ 1) < hq ? p1 : 0u) + ((hq ^ 2) < hq ? p2 : 0u) + ((hq ^ 3) < hq ? p3 : 0u);
+    int pos = cnt + (int)(before & 255u);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      if (e == 4) pos = cnt + (int)(all & 255u) + (int)(before >> 8);
+      const bool take = (takes >> e) & 1u;
+      const int at = take ? pos : BSF_CAP + hq;              // an entry that does not enter goes behind the list (a slot per lane)
+      keys[at] = max(order_key(sc[e]), 1u);
+      idx[at] = (unsigned short)(kb + 16 * (e >> 2) + 4 * hq + (e & 3));
+      pos += take;
+    }
+    cnt += (int)(all & 255u) + (int)(all >> 8);
+  };
+
+  fetch(0);
+  for (int t = 0; t < n_tiles; ++t) {
+    MINF_WAIT_VMCNT(0);
+    __syncthreads();                                         // tile t landed; every wave is done with tile t-1
+    if (t + 1 < n_tiles) fetch(t + 1);
+    if (t > t_last) continue;                                // no key of the tile is causal for this wave
+    const int kb = 32 * t;
+    // logits of the tile's two 16-key blocks, two accumulation chains each
+    const char *tile = lds + (t & 1) * BSF_TILE_BYTES + n * 512;
+    f32x4v acc[2][2];
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int c = 0; c < 2; ++c) acc[b][c] = f32x4v{0.f, 0.f, 0.f, 0.f};
+    float4 a0[8], a1[8];                                     // all of the tile's operands first: one LDS latency, not eight
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int ch = ((8 * hq + i) ^ n) << 4;                // rows n and 16 + n share n % 16
+      a0[i] = *reinterpret_cast<const float4 *>(tile + ch);
+      a1[i] = *reinterpret_cast<const float4 *>(tile + 16 * 512 + ch);
+    }
+    __builtin_amdgcn_sched_barrier(0);                       // keeps the loads up here, ahead of the MFMAs
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0[i].x, q[4 * i], acc[0][0], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[i].x, q[4 * i], acc[1][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0[i].y, q[4 * i + 1], acc[0][1], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[i].y, q[4 * i + 1], acc[1][1], 0, 0, 0);
+      acc[0][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0[i].z, q[4 * i + 2], acc[0][0], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[i].z, q[4 * i + 2], acc[1][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0[i].w, q[4 * i + 3], acc[0][1], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1[i].w, q[4 * i + 3], acc[1][1], 0, 0, 0);
+    }
+    float sc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) sc[e] = acc[e >> 2][0][e & 3] + acc[e >> 2][1][e & 3];
+    select(sc, kb);
+  }
+  // exact selection of what is left, then the row goes out (ascending; -1 behind the last entry)
+  cnt = bsf_compact(keys, idx, cnt, k, true, hq, tau).cnt;
+  if (row_ok) {
+    int32_t *out = blk_idx + ((int64_t)slot * NB + row) * topk;
+    for (int i = hq; i < topk; i += 4) out[i] = i < cnt ? (int32_t)idx[i] : -1;
+    if (hq == 0) blk_cnt[(int64_t)slot * NB + row] = cnt;
+  }
+}
+
 // Processing order of the query blocks of one head: sorted by (first kept key block, block id).
 // One workgroup per head: the composite keys (first << 16 | block) of up to 32768 blocks are
 // sorted in LDS (4 bytes per block, up to 128 KiB) by a bitonic network (padded to a power of
@@ -1358,11 +1701,16 @@ static int bs_head_batch(int NB, int n_heads) {
   return (int)(hb < (size_t)n_heads ? hb : (size_t)n_heads);
 }
 
-size_t bs_index_ws_bytes(int N, int n_heads) {
+static int bs_rows_padded(int NB) { return (NB + 31) / 32 * 32; }
+static bool bs_fused(int NB, int topk) { return topk <= BSF_MAX_TOPK && NB < 65536; }
+
+size_t bs_index_ws_bytes(int N, int n_heads, int topk) {
   const int NB = N / 64;
   size_t b = 0;
-  b += 2 * align256((size_t)n_heads * NB * 128 * sizeof(float));              // pooled Q, pooled K
-  b += align256((size_t)bs_head_batch(NB, n_heads) * NB * NB * sizeof(float)); // block logits
+  b += align256((size_t)n_heads * NB * 128 * sizeof(float));                   // pooled Q
+  b += align256((size_t)n_heads * bs_rows_padded(NB) * 128 * sizeof(float));   // pooled K, whole 32-row tiles
+  if (!bs_fused(NB, topk))
+    b += align256((size_t)bs_head_batch(NB, n_heads) * NB * NB * sizeof(float)); // block logits
   return b;
 }
 
@@ -1385,19 +1733,30 @@ hipError_t launch_build_bs(const QKV &x, const HeadList &hl, int topk, int32_t *
   }
   for (int i = hl.n; i < MINF_MAX_HEADS; ++i) km.slot_kv[i] = 0;
   for (int i = km.n_kv; i < MINF_MAX_HEADS; ++i) km.kv[i] = 0;
+  const int NBp = bs_rows_padded(NB);
   char *p = static_cast<char *>(ws);
   float *qpool = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * NB * 128 * sizeof(float));
-  float *kpool = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * NB * 128 * sizeof(float));
+  float *kpool = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * NBp * 128 * sizeof(float));
   float *scores = reinterpret_cast<float *>(p);
-  hipLaunchKernelGGL(bs_pool_kernel, dim3(NB, hl.n + km.n_kv), dim3(256), 0, st, x, hl, km, qpool, kpool);
-  const int hbmax = bs_head_batch(NB, hl.n);
-  const int TB = (NB + 63) / 64, n_tiles = TB * (TB + 1) / 2;
-  for (int s0 = 0; s0 < hl.n; s0 += hbmax) {
-    const int hb = hl.n - s0 < hbmax ? hl.n - s0 : hbmax;
-    hipLaunchKernelGGL(bs_logits_kernel, dim3(n_tiles, hb), dim3(64), 0, st, NB, s0, km,
-                       (const float *)qpool, (const float *)kpool, scores, x.scale);
-    hipLaunchKernelGGL(bs_select_kernel, dim3(NB, hb), dim3(256), 0, st, NB, s0, topk,
-                       (const float *)scores, blk_idx, blk_cnt);
+  hipLaunchKernelGGL(bs_pool_kernel, dim3(NB, hl.n + km.n_kv), dim3(256), 0, st, x, hl, km, qpool, kpool, NBp);
+  if (bs_fused(NB, topk)) {
+    // block logits and top-k in one kernel: nothing of size NB x NB is stored
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs_topk_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)BSF_LDS);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(bs_topk_kernel, dim3(hl.n, (NB + BSF_ROWS - 1) / BSF_ROWS), dim3(BSF_THREADS), BSF_LDS, st, NB, NBp,
+                       topk, km, (const float *)qpool, (const float *)kpool, blk_idx, blk_cnt);
+  } else {
+    // budgets beyond the candidate lists of the fused kernel: logits through memory, head batches
+    const int hbmax = bs_head_batch(NB, hl.n);
+    const int TB = (NB + 63) / 64, n_tiles = TB * (TB + 1) / 2;
+    for (int s0 = 0; s0 < hl.n; s0 += hbmax) {
+      const int hb = hl.n - s0 < hbmax ? hl.n - s0 : hbmax;
+      hipLaunchKernelGGL(bs_logits_kernel, dim3(n_tiles, hb), dim3(64), 0, st, NB, NBp, s0, km,
+                         (const float *)qpool, (const float *)kpool, scores, x.scale);
+      hipLaunchKernelGGL(bs_select_kernel, dim3(NB, hb), dim3(256), 0, st, NB, s0, topk,
+                         (const float *)scores, blk_idx, blk_cnt);
+    }
   }
   if (order) {
     if (NB <= BS_ORDER_MAX) {

@@ -120,9 +120,9 @@ size_t minf_vs_index_workspace_bytes(const minf_qkv *x, int32_t n_heads, int32_t
   return vs_index_ws_bytes(x->seq_len, n_heads);
 }
 
-size_t minf_bs_index_workspace_bytes(const minf_qkv *x, int32_t n_heads) {
-  if (check_qkv(x, false) != MINF_OK || n_heads < 1 || n_heads > MINF_MAX_HEADS) return 0;
-  return bs_index_ws_bytes(x->seq_len, n_heads);
+size_t minf_bs_index_workspace_bytes(const minf_qkv *x, int32_t n_heads, int32_t topk) {
+  if (check_qkv(x, false) != MINF_OK || n_heads < 1 || n_heads > MINF_MAX_HEADS || topk < 1) return 0;
+  return bs_index_ws_bytes(x->seq_len, n_heads, topk);
 }
 
 static minf_status build_vs_common(const minf_qkv *x, const int32_t *heads, int32_t n_heads, int32_t last_q,
@@ -192,7 +192,7 @@ minf_status minf_build_bs_index(const minf_qkv *x, const int32_t *heads, int32_t
   if (topk < 1) return MINF_ERR_BUDGET;
   if (!out || !out->blk_idx || !out->blk_cnt) return MINF_ERR_NULL;
   if (out->topk != topk || out->block != block) return MINF_ERR_BUDGET;
-  const size_t need = bs_index_ws_bytes(x->seq_len, n_heads);
+  const size_t need = bs_index_ws_bytes(x->seq_len, n_heads, topk);
   if (!ws || ws_bytes < need) return MINF_ERR_WORKSPACE;
   if (reinterpret_cast<uintptr_t>(ws) % 256 != 0) return MINF_ERR_WORKSPACE;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);

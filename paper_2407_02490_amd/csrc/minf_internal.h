@@ -108,7 +108,7 @@ hipError_t launch_vs(const QKV &x, const HeadList &hl, const int32_t *v_idx, con
 
 // index launches (index_kernels.hip)
 size_t vs_index_ws_bytes(int N, int n_heads);
-size_t bs_index_ws_bytes(int N, int n_heads);
+size_t bs_index_ws_bytes(int N, int n_heads, int topk);
 hipError_t launch_build_vs(const QKV &x, const HeadList &hl, int last_q, int nv, int ns,
                            int32_t *v_idx, int32_t *s_idx, int32_t *cover, uint32_t *cover_bits,
                            int32_t *counts, int cover_words, void *ws, hipStream_t st);

@@ -88,7 +88,7 @@ def test_c3_block_sparse_128k(B):
     c, N = x.meta, x.seq_len
     heads = list(range(x.n_q_heads))
     idx = B.alloc_bs_index(len(heads), N, c["topk"])
-    ws = torch.empty(B.minf_bs_index_workspace_bytes(x.q, x.k, len(heads)), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(B.minf_bs_index_workspace_bytes(x.q, x.k, len(heads), c["topk"]), dtype=torch.uint8, device="cuda")
     o = torch.empty_like(x.q)
     B.minf_build_bs_index(x.q, x.k, heads, c["topk"], idx, ws)
     B.minf_bs_attn(x.q, x.k, x.v, o, heads, idx)
@@ -118,7 +118,7 @@ def test_c4_mixed_1m(B):
     vsi = B.alloc_vs_index(len(vs_h), c["nv"], c["ns"], N)
     vws = torch.empty(B.minf_vs_index_workspace_bytes(x.q, x.k, len(vs_h), c["last_q"]), dtype=torch.uint8, device="cuda")
     bsi = B.alloc_bs_index(len(bs_h), N, c["topk"])
-    bws = torch.empty(B.minf_bs_index_workspace_bytes(x.q, x.k, len(bs_h)), dtype=torch.uint8, device="cuda")
+    bws = torch.empty(B.minf_bs_index_workspace_bytes(x.q, x.k, len(bs_h), c["topk"]), dtype=torch.uint8, device="cuda")
     o = torch.full_like(x.q, float("nan"))
     B.minf_build_vs_index(x.q, x.k, vs_h, c["last_q"], c["nv"], c["ns"], vsi, vws)
     B.minf_build_bs_index(x.q, x.k, bs_h, c["topk"], bsi, bws)
@@ -197,7 +197,7 @@ def test_ragged_medium_length_mixed(B):
     vsi = B.alloc_vs_index(len(heads_vs), nv, ns, N)
     vws = torch.empty(B.minf_vs_index_workspace_bytes(x.q, x.k, len(heads_vs), 64), dtype=torch.uint8, device="cuda")
     bsi = B.alloc_bs_index(len(heads_bs), N, topk)
-    bws = torch.empty(B.minf_bs_index_workspace_bytes(x.q, x.k, len(heads_bs)), dtype=torch.uint8, device="cuda")
+    bws = torch.empty(B.minf_bs_index_workspace_bytes(x.q, x.k, len(heads_bs), topk), dtype=torch.uint8, device="cuda")
     o = torch.full_like(x.q, float("nan"))
     B.minf_build_vs_index(x.q, x.k, heads_vs, 64, nv, ns, vsi, vws)
     B.minf_build_bs_index(x.q, x.k, heads_bs, topk, bsi, bws)
@@ -243,7 +243,7 @@ def test_two_million_tokens_one_head(B):
     vsi = B.alloc_vs_index(1, nv, ns, N)
     vws = torch.empty(B.minf_vs_index_workspace_bytes(x.q, x.k, 1, 64), dtype=torch.uint8, device="cuda")
     bsi = B.alloc_bs_index(1, N, topk)
-    bws = torch.empty(B.minf_bs_index_workspace_bytes(x.q, x.k, 1), dtype=torch.uint8, device="cuda")
+    bws = torch.empty(B.minf_bs_index_workspace_bytes(x.q, x.k, 1, topk), dtype=torch.uint8, device="cuda")
     o = torch.full_like(x.q, float("nan"))
     B.minf_build_vs_index(x.q, x.k, [0], 64, nv, ns, vsi, vws)
     B.minf_build_bs_index(x.q, x.k, [1], topk, bsi, bws)

@@ -248,6 +248,35 @@ def test_bs_index_equal_logits_keep_the_lowest_blocks(B, NB, topk):
     assert np.array_equal(got, want)
 
 
+@pytest.mark.parametrize("topk", [100, 112, 113])
+def test_bs_index_several_workgroups_ragged_tail(B, topk):
+    """421 query blocks: four workgroups of the fused logits + top-k kernel, the last one ragged, rows long
+    enough for many cuts of their candidate lists; 112 is the largest budget that kernel takes, 113 goes
+    through the stored logits."""
+    q, k, v = random_qkv(17, 2, 1, 64 * 421)
+    idx = build_bs(B, q, k, [1, 0], topk)
+    check_bs_index(idx, 0, to_f64(q[1]), to_f64(k[0]), topk)
+    check_bs_index(idx, 1, to_f64(q[0]), to_f64(k[0]), topk)
+
+
+def test_bs_index_few_distinct_logits(B):
+    """Key blocks drawn from five distinct ones: every row sees five logit values, each many times over, so
+    every cut of a candidate list lands on a value with far more equal entries than it may keep, and the
+    kept ones must be the lowest blocks.  Equal blocks give bit-equal logits: the result is the oracle's."""
+    NB, topk = 700, 100
+    g = torch.Generator().manual_seed(23)
+    q = torch.randn(1, 64 * NB, 128, generator=g).to(torch.bfloat16)
+    proto = torch.randn(5, 64, 128, generator=g).to(torch.bfloat16)
+    pick = torch.randint(0, 5, (NB,), generator=g)
+    k = proto[pick].reshape(1, 64 * NB, 128)
+    idx = build_bs(B, q.cuda(), k.cuda(), [0], topk)
+    io, co, _ = O.bs_index(to_f64(q[0]), to_f64(k[0]), 64, topk)
+    assert np.array_equal(idx.blk_cnt[0].cpu().numpy(), co)
+    got = idx.blk_idx[0].cpu().numpy()
+    for b in range(NB):
+        assert np.array_equal(got[b, :co[b]], np.sort(io[b, :co[b]])), b
+
+
 def test_bs_index_budget_above_256_blocks(B):
     """A budget larger than the number of threads of the selection workgroup."""
     q, k, v = random_qkv(15, 2, 1, 64 * 400)
