@@ -23,7 +23,9 @@ namespace minf {
 
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 
-constexpr int VS_CHUNK = 1024;      // keys / offsets owned by one workgroup of the score kernels
+constexpr int VS_CHUNK = 1024;      // keys / offsets owned by one workgroup of the score kernels ...
+constexpr int VS_CHUNK_SHORT = 256;  // ... and for sequences up to VS_SHORT_N, where 1024 would leave most of the chip idle
+constexpr int VS_SHORT_N = 32768;
 
 struct KvMap {                      // pooling work list of the Block-Sparse build
   int32_t n_kv;                     // distinct KV heads used by the call
@@ -351,7 +353,7 @@ __device__ inline void block_scan2_256(int a, int b, int *ea, int *eb, int *ta, 
 constexpr int VS_TILE_BYTES = TILE_BYTES;          // 16 KiB
 constexpr int VS_DPAD = 96;                       // slack on both sides of the chunk's diagonal sums
 constexpr int VS_SKEW_PITCH = 64;                 // floats per row of the skewed probability tile (32 rows x 32 keys)
-constexpr int VS_WAVE_FLOATS = VS_CHUNK + 2 * VS_DPAD + 32 * VS_SKEW_PITCH;   // pass 2, private to a wave
+constexpr int vs_wave_floats(int C) { return C + 2 * VS_DPAD + 32 * VS_SKEW_PITCH; }   // pass 2, private to a wave
 
 // This wave's quarter of a K tile of ROWS rows (64 or 32) that lies wholly inside [0, N).
 template <int ROWS>
@@ -402,7 +404,7 @@ __device__ inline void vs_skew_reduce(const float (&p)[16], float *skew, float *
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int PASS>
+template <int PASS, int C>
 __global__ __launch_bounds__(256, 2) void vs_score_kernel(QKV x, HeadList hl, VsGroups vg, int last_q, int n_chunks,
                                                        float *ml_part, const float *ml_fin,
                                                        float *colsum, float *diagsum) {
@@ -415,14 +417,14 @@ __global__ __launch_bounds__(256, 2) void vs_score_kernel(QKV x, HeadList hl, Vs
   const bool active = wave < vg.cnt[grp];
   // a wave without a head takes the group's first one for its addresses; it only helps to fetch
   const int slot = __builtin_amdgcn_readfirstlane((int)vg.slot[grp][active ? wave : 0]);
-  float *dacc = reinterpret_cast<float *>(lds + 3 * HALF_BYTES) + wave * VS_WAVE_FLOATS;   // [VS_DPAD + VS_CHUNK + VS_DPAD], pass 2
-  float *skew = dacc + VS_CHUNK + 2 * VS_DPAD;                         // [32][VS_SKEW_PITCH], pass 2
+  float *dacc = reinterpret_cast<float *>(lds + 3 * HALF_BYTES) + wave * vs_wave_floats(C);   // [VS_DPAD + C + VS_DPAD], pass 2
+  float *skew = dacc + C + 2 * VS_DPAD;                                // [32][VS_SKEW_PITCH], pass 2
 
   const int head = __builtin_amdgcn_readfirstlane(hl.h[slot]);
   const int kvh = to_sgpr(head / x.group);
   const bf16_t *qh = x.q + head * x.q_sh, *kh = x.k + kvh * x.k_sh;
   const int n = lane & 31, h = lane >> 5;
-  const int N = x.N, C = VS_CHUNK;
+  const int N = x.N;
   const int r_min = 64 - last_q;
 
   // Q fragments: lane (n, h) holds Q[N-64 + 32 nb + n][16 ks + 8 h .. +7], which is the B operand
@@ -1604,7 +1606,8 @@ __global__ __launch_bounds__(1024) void bs_order_kernel(int NB, int topk, const 
 // ---------------------------------------------------------------------------
 static inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
-static int vs_chunks(int N) { return (N + VS_CHUNK - 1) / VS_CHUNK; }
+static int vs_chunk_keys(int N) { return N <= VS_SHORT_N ? VS_CHUNK_SHORT : VS_CHUNK; }
+static int vs_chunks(int N) { return (N + vs_chunk_keys(N) - 1) / vs_chunk_keys(N); }
 
 static int vs_slices(int N) { return (N + VS_SLICE - 1) / VS_SLICE; }
 static int vs_cand_cap(int N) { return N / 4 > 1024 ? N / 4 : 1024; }        // candidates per (head, which)
@@ -1652,17 +1655,24 @@ hipError_t launch_build_vs(const QKV &x, const HeadList &hl, int last_q, int nv,
     vg.slot[g][vg.cnt[g]++] = (uint8_t)i;
   }
   // 48 KiB (three workgroups of four waves per CU; registers allow two) and 75 KiB (two per CU)
-  const size_t lds1 = 3 * VS_TILE_BYTES;
-  const size_t lds2 = 3 * HALF_BYTES + VS_GROUP * VS_WAVE_FLOATS * sizeof(float);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(vs_score_kernel<2>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
-  if (e != hipSuccess) return e;
   const dim3 grid(nc, vg.n);
-  hipLaunchKernelGGL(vs_score_kernel<1>, grid, dim3(256), lds1, st, x, hl, vg, last_q, nc, ml_part,
-                     (const float *)nullptr, (float *)nullptr, (float *)nullptr);
-  hipLaunchKernelGGL(vs_combine_kernel, dim3(hl.n), dim3(1024), 0, st, nc, (const float *)ml_part, ml_fin);
-  hipLaunchKernelGGL(vs_score_kernel<2>, grid, dim3(256), lds2, st, x, hl, vg, last_q, nc, (float *)nullptr,
-                     (const float *)ml_fin, colsum, diagsum);
+  auto score = [&](auto chunk_keys) -> hipError_t {
+    constexpr int C = decltype(chunk_keys)::value;
+    const size_t lds1 = 3 * VS_TILE_BYTES;
+    const size_t lds2 = 3 * HALF_BYTES + VS_GROUP * vs_wave_floats(C) * sizeof(float);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(vs_score_kernel<2, C>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds2);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL((vs_score_kernel<1, C>), grid, dim3(256), lds1, st, x, hl, vg, last_q, nc, ml_part,
+                       (const float *)nullptr, (float *)nullptr, (float *)nullptr);
+    hipLaunchKernelGGL(vs_combine_kernel, dim3(hl.n), dim3(1024), 0, st, nc, (const float *)ml_part, ml_fin);
+    hipLaunchKernelGGL((vs_score_kernel<2, C>), grid, dim3(256), lds2, st, x, hl, vg, last_q, nc, (float *)nullptr,
+                       (const float *)ml_fin, colsum, diagsum);
+    return hipSuccess;
+  };
+  const hipError_t e = vs_chunk_keys(N) == VS_CHUNK_SHORT ? score(std::integral_constant<int, VS_CHUNK_SHORT>{})
+                                                         : score(std::integral_constant<int, VS_CHUNK>{});
+  if (e != hipSuccess) return e;
   // top-k of the line scores: prefilter by many workgroups, exact selection on what is left
   const int kv_ = nv < N ? nv : N, ks_ = ns < N ? ns : N;
   const int log_gv = vs_log_group(N, kv_), log_gs = vs_log_group(N, ks_);
