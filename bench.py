@@ -174,12 +174,18 @@ class Layer:
                 kv = len({h // (self.Hq // self.x.n_kv_heads) for h in self.vs_heads})
                 by = kv * self.N * 256 + len(self.vs_heads) * (64 * 256 + 2 * self.N * 4)
                 e.update({"algorithmic_bytes": by, "gb_per_s": round(by / (e["ms"] * 1e-3) / 1e9, 1),
-                          "k_passes_run": "2 per query head (row max/sum, then normalised sums)"})
+                          "k_passes_run": "2 per K/V head in use (row max/sum, then normalised sums), "
+                                          "each shared by the query heads of the group",
+                          "workspace_mib": round(self.vs_ws.numel() / 2**20, 1)})
             if k == "bs_index":
                 # all of Q of the heads and K of their K/V heads, once
                 kv = len({h // (self.Hq // self.x.n_kv_heads) for h in self.bs_heads})
                 by = (len(self.bs_heads) + kv) * self.N * 256
-                e.update({"algorithmic_bytes": by, "gb_per_s": round(by / (e["ms"] * 1e-3) / 1e9, 1)})
+                nb = self.N // 64
+                fl = len(self.bs_heads) * nb * (nb + 1) // 2 * 256          # causal block logits, fp32, d = 128
+                e.update({"algorithmic_bytes": by, "gb_per_s": round(by / (e["ms"] * 1e-3) / 1e9, 1),
+                          "logit_flop": fl, "fp32_tflops": round(fl / (e["ms"] * 1e-3) / 1e12, 2),
+                          "workspace_mib": round(self.bs_ws.numel() / 2**20, 1)})
             if k in tiles:
                 # tiles: canonical 64 x 64 decomposition of the mask (the cost model's unit);
                 # executed_tiles: what the kernel computes (VS: 32-key steps); the rate uses the latter

@@ -1262,10 +1262,30 @@ typedef __attribute__((address_space(3))) u32x2 lds_u32x2;
 
 constexpr int BSF_GROUPS = BSF_CAP / 16;            // 4-entry groups of a list that one of the row's four lanes holds
 
-// sum over the four lanes of a row
+// Exchanges between the four lanes of a row (n, n + 16, n + 32, n + 48) by the lane-swap instructions
+// of the vector ALU, not through the LDS crossbar, whose round trip each exchange would wait for.
+// permlane16_swap(a, b) swaps the odd 16-lane rows of a with the even rows of b, permlane32_swap(a, b)
+// the upper half of a with the lower half of b; with a = b = v the two results are (own, partner) in
+// the lanes of an even row / the lower half and (partner, own) in the others.
+__device__ __forceinline__ unsigned bsf_xor16(unsigned v) {
+  const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+  return (threadIdx.x & 16) ? r[0] : r[1];
+}
+__device__ __forceinline__ unsigned bsf_xor32(unsigned v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+  return (threadIdx.x & 32) ? r[0] : r[1];
+}
 __device__ __forceinline__ int bsf_row_sum(int v) {
-  v += __shfl_xor(v, 16);
-  return v + __shfl_xor(v, 32);
+  const auto r = __builtin_amdgcn_permlane16_swap((unsigned)v, (unsigned)v, false, false);
+  const unsigned u = r[0] + r[1];
+  const auto t = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return (int)(t[0] + t[1]);
+}
+__device__ __forceinline__ unsigned bsf_row_max(unsigned v) {
+  const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+  const unsigned u = max(r[0], r[1]);
+  const auto t = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return max(t[0], t[1]);
 }
 
 // Serial form of the cut below, for a row whose entries equal to T are more than it may keep: of
@@ -1327,8 +1347,7 @@ __device__ __noinline__ BsfCut bsf_compact(lds_u32 *keys, lds_u16 *idx, int cnt,
       hi = max(hi, kv[g][c]);
     }
   }
-  hi = max(hi, (unsigned)__shfl_xor((int)hi, 16));
-  hi = max(hi, (unsigned)__shfl_xor((int)hi, 32));
+  hi = bsf_row_max(hi);
   auto count_ge = [&](unsigned v) {
     int c = 0;
 #pragma unroll
@@ -1366,7 +1385,7 @@ __device__ __noinline__ BsfCut bsf_compact(lds_u32 *keys, lds_u16 *idx, int cnt,
       const int above = T == 0xffffffffu ? 0 : count_ge(T + 1u);
       serial_cnt = bsf_cut_serial(keys, idx, cnt, T, k - above, hq);
     }
-    serial_cnt = __shfl(serial_cnt, threadIdx.x & 15);         // from the row's first lane
+    serial_cnt = (int)bsf_row_max(hq == 0 ? (unsigned)serial_cnt : 0u);   // from the row's first lane
   }
   // kept entries per group: prefix over this lane's groups, exclusive and inclusive, one byte each
   unsigned excl[3] = {0u, 0u, 0u}, incl[3] = {0u, 0u, 0u};
@@ -1389,9 +1408,10 @@ __device__ __noinline__ BsfCut bsf_compact(lds_u32 *keys, lds_u16 *idx, int cnt,
     const bool lower = hq < (hq ^ x);                          // this lane comes before its partner
 #pragma unroll
     for (int w = 0; w < 3; ++w) {
-      const unsigned send = lower ? incl[w] : excl[w];
-      const int lane_x = 16 * x;
-      at_pk[w] += (unsigned)__shfl_xor((int)send, lane_x);
+      unsigned got = lower ? incl[w] : excl[w];
+      if (x & 1) got = bsf_xor16(got);
+      if (x & 2) got = bsf_xor32(got);
+      at_pk[w] += got;
     }
   }
 #pragma unroll
@@ -1488,22 +1508,29 @@ __global__ __launch_bounds__(BSF_THREADS) void bs_topk_kernel(int NB, int NBp, i
     // it must is cut down with it (the rows then fill up together: one cut where the wave would
     // pay for sixteen), and what the raised bars exclude leaves the tile's share.  A cut leaves a
     // row at most BSF_CAP - 32 entries, so its share fits.
-    if (__builtin_amdgcn_ballot_w64(cnt + bsf_row_sum(__builtin_popcount(takes)) > BSF_CAP)) {
+    // (counts of the tile's two 16-key blocks, one byte each, from all four lanes: of the lanes hq ^ 1, hq ^ 2, hq ^ 3)
+    unsigned mine = (unsigned)__builtin_popcount(takes & 15u) | (unsigned)__builtin_popcount(takes >> 4) << 8;
+    unsigned p1 = bsf_xor16(mine), p2 = bsf_xor32(mine), p3 = bsf_xor32(p1);
+    unsigned all = mine + p1 + p2 + p3;
+    if (__builtin_amdgcn_ballot_w64(cnt + (int)(all & 255u) + (int)(all >> 8) > BSF_CAP)) {
       const BsfCut c = bsf_compact(keys, idx, cnt, k, false, hq, tau);
       cnt = c.cnt; tau = c.tau;
       asm volatile("" ::: "memory");
       bsf_load_q(qp, q);
+      // wait for them here (vmcnt 0, other counters untouched), in a form the compiler's own bookkeeping
+      // sees: otherwise every use of q in the tile loop waits on the memory counter, which also
+      // counts the tile load just issued, and the loop runs at the latency of that load
+      __builtin_amdgcn_s_waitcnt(0x0F70);
       bar = bsf_bar_value(tau);
 #pragma unroll
       for (int e = 0; e < 8; ++e)
         if (!(sc[e] > bar)) takes &= ~(1u << e);
+      mine = (unsigned)__builtin_popcount(takes & 15u) | (unsigned)__builtin_popcount(takes >> 4) << 8;
+      p1 = bsf_xor16(mine); p2 = bsf_xor32(mine); p3 = bsf_xor32(p1);
+      all = mine + p1 + p2 + p3;
     }
     // list order = key-block order: within a 16-key block the four lanes of the row follow each
-    // other with four keys each.  Counts of the two blocks, one byte each, from all four lanes.
-    const unsigned mine = (unsigned)__builtin_popcount(takes & 15u) | (unsigned)__builtin_popcount(takes >> 4) << 8;
-    const unsigned p1 = (unsigned)__shfl_xor((int)mine, 16), p2 = (unsigned)__shfl_xor((int)mine, 32);
-    const unsigned p3 = (unsigned)__shfl_xor((int)p1, 32);    // of the lanes hq ^ 1, hq ^ 2, hq ^ 3
-    const unsigned all = mine + p1 + p2 + p3;
+    // other with four keys each
     const unsigned before = ((hq ^ 1) < hq ? p1 : 0u) + ((hq ^ 2) < hq ? p2 : 0u) + ((hq ^ 3) < hq ? p3 : 0u);
     int pos = cnt + (int)(before & 255u);
 #pragma unroll
@@ -1520,7 +1547,7 @@ __global__ __launch_bounds__(BSF_THREADS) void bs_topk_kernel(int NB, int NBp, i
 
   fetch(0);
   for (int t = 0; t < n_tiles; ++t) {
-    MINF_WAIT_VMCNT(0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0), as an instruction the compiler's own counting sees (see below)
     __syncthreads();                                         // tile t landed; every wave is done with tile t-1
     if (t + 1 < n_tiles) fetch(t + 1);
     if (t > t_last) continue;                                // no key of the tile is causal for this wave
