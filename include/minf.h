@@ -157,7 +157,7 @@ minf_status minf_build_vs_index(const minf_qkv *x, const int32_t *heads, int32_t
  * written by the same call).  The array's device address is looked up on the
  * first call on each device (MINF_ERR_HIP if the runtime refuses).
  */
-#define MINF_NOALLOC_SCRATCH_BYTES (64u << 20)
+#define MINF_NOALLOC_SCRATCH_BYTES (96u << 20)   /* 32 heads at 128K tokens need 74 MiB */
 minf_status minf_build_vs_index_noalloc(const minf_qkv *x, const int32_t *heads, int32_t n_heads,
                                         int32_t last_q, int32_t nv, int32_t ns, int32_t block,
                                         minf_vs_index *out, void *hip_stream);

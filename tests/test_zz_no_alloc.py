@@ -51,7 +51,7 @@ def test_noalloc_entry_matches_the_workspace_entry_twice_in_a_row(B):
 
 
 def test_noalloc_entry_refuses_sizes_beyond_its_scratch_array(B):
-    N = 1 << 20                                  # 16 heads x 1M tokens need 2 x 64 MiB of line scores
+    N = 1 << 20                                  # 16 heads x 1M tokens need 296 MiB of workspace, the array holds 96
     q = torch.empty(16, N, 128, dtype=torch.bfloat16, device="cuda")
     k = torch.empty(4, N, 128, dtype=torch.bfloat16, device="cuda")
     idx = B.alloc_vs_index(16, 8, 8, N)
