@@ -66,3 +66,36 @@ def test_vs_index_from_lines_rejects_bad_arguments_on_the_host(lib):
     assert lib.minf_vs_index_from_lines(1024, 1, ctypes.byref(idx), None) == 5
     idx.block, idx.ns = 64, 0
     assert lib.minf_vs_index_from_lines(1024, 1, ctypes.byref(idx), None) == 3
+
+
+def _qkv(N, n_q=32, n_kv=8):
+    from paper_2407_02490_amd.binding import _QKV
+    x = _QKV()
+    x.q = x.k = x.v = x.o = 4096                                                        # never dereferenced
+    for name, h in (("q_stride", n_q), ("k_stride", n_kv), ("v_stride", n_kv), ("o_stride", n_q)):
+        st = getattr(x, name)
+        st[0], st[1], st[2] = h * N * 128, N * 128, 128
+    x.batch, x.n_q_heads, x.n_kv_heads, x.seq_len, x.head_dim, x.softmax_scale = 1, n_q, n_kv, N, 128, 0.0
+    return x
+
+
+def test_workspace_sizes(lib):
+    """Host arithmetic only.  The Block-Sparse build stores no block logits up to a budget of 112 blocks
+    (Alg. 3's top-k is then fused with the logits): pooled Q and K alone, 512 bytes per head and block each."""
+    lib.minf_bs_index_workspace_bytes.restype = ctypes.c_size_t
+    lib.minf_vs_index_workspace_bytes.restype = ctypes.c_size_t
+    x = _qkv(1 << 20)
+    NB = (1 << 20) // 64
+    fused = lib.minf_bs_index_workspace_bytes(ctypes.byref(x), 6, 100)
+    assert fused == 2 * 6 * NB * 512
+    assert lib.minf_bs_index_workspace_bytes(ctypes.byref(x), 6, 112) == fused
+    staged = lib.minf_bs_index_workspace_bytes(ctypes.byref(x), 6, 113)
+    assert staged >= fused + 2 * NB * NB * 4                                            # at least two heads' logits
+    assert lib.minf_bs_index_workspace_bytes(ctypes.byref(x), 6, 0) == 0
+    assert lib.minf_bs_index_workspace_bytes(ctypes.byref(x), 0, 100) == 0
+    # ragged number of blocks: pooled K is padded to whole 32-row tiles
+    y = _qkv(64 * 33)
+    assert lib.minf_bs_index_workspace_bytes(ctypes.byref(y), 1, 8) == 33 * 512 + 64 * 512
+    # Vertical-Slash: grows with heads x tokens, within 16 .. 24 bytes per head and token
+    per = lib.minf_vs_index_workspace_bytes(ctypes.byref(x), 24, 64) / (24 * (1 << 20))
+    assert 16 <= per <= 24
