@@ -4,17 +4,24 @@
 //   A_hat = softmax(Q[-64:] K^T / sqrt(d) + causal), column sums, diagonal sums,
 //   exact top-k of both, ascending sort, merge of the 64-wide slash tiles into
 //   offset runs + a run bitmap.
-//   K is streamed twice: pass 1 gives the row max / row sum of the 64 estimating
-//   queries per key chunk (combined afterwards in a fixed order), pass 2 forms
-//   the normalised probabilities and reduces them along columns and diagonals.
+//   K is streamed twice per K/V head (the query heads of a group share every K
+//   tile): pass 1 gives the row max / row sum of the 64 estimating queries per
+//   key chunk (combined afterwards in a fixed order), pass 2 forms the
+//   normalised probabilities and reduces them along columns and diagonals.
 //   A_hat itself (64 x N) is never stored.  All reductions run in a fixed
 //   order: the scores are bit-reproducible.
+//   Top-k of the line scores: an exact radix select on the order-preserving
+//   integer image of the fp32 score (4 passes of 8 bits), ties to the lower
+//   index, followed by an ordered compaction, so the kept indices come out
+//   ascending without a sort.  From 128K scores on, a prefilter by many
+//   workgroups (group maxima -> a lower bound of the k-th largest -> the scores
+//   that reach it) leaves the select a few thousand candidates.
 // Block-Sparse (Alg. 3, first steps):
-//   mean pooling of Q and K over 64-token blocks (fp32), block logits with the
-//   fp32 MFMA (the selection needs fp32-class logits), per-row exact top-k.
-// Top-k is an exact radix select on the order-preserving integer image of the
-// fp32 score (4 passes of 8 bits), ties to the lower index, followed by an
-// ordered compaction, so the kept indices come out ascending without a sort.
+//   mean pooling of Q and K over 64-token blocks (fp32); block logits with the
+//   fp32 MFMA (the selection needs fp32-class logits) and the per-row top-k in
+//   one kernel: candidate lists behind a rising bar, cut by bisection, exact
+//   at the end; the logits are never stored.  Budgets above 112 blocks go
+//   through stored logits and a per-row radix select.
 #include <string.h>
 
 #include "mfma_tile.h"
