@@ -31,8 +31,10 @@ namespace minf {
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 
 constexpr int VS_CHUNK = 1024;      // keys / offsets owned by one workgroup of the score kernels ...
-constexpr int VS_CHUNK_SHORT = 256;  // ... and for sequences up to VS_SHORT_N, where 1024 would leave most of the chip idle
+constexpr int VS_CHUNK_SHORT = 256;  // ... for sequences up to VS_SHORT_N, where 1024 would leave most of the chip idle,
 constexpr int VS_SHORT_N = 32768;
+constexpr int VS_CHUNK_TINY = 128;   // ... and up to VS_TINY_N
+constexpr int VS_TINY_N = 8192;
 
 struct KvMap {                      // pooling work list of the Block-Sparse build
   int32_t n_kv;                     // distinct KV heads used by the call
@@ -1640,7 +1642,7 @@ __global__ __launch_bounds__(1024) void bs_order_kernel(int NB, int topk, const 
 // ---------------------------------------------------------------------------
 static inline size_t align256(size_t v) { return (v + 255) / 256 * 256; }
 
-static int vs_chunk_keys(int N) { return N <= VS_SHORT_N ? VS_CHUNK_SHORT : VS_CHUNK; }
+static int vs_chunk_keys(int N) { return N <= VS_TINY_N ? VS_CHUNK_TINY : N <= VS_SHORT_N ? VS_CHUNK_SHORT : VS_CHUNK; }
 static int vs_chunks(int N) { return (N + vs_chunk_keys(N) - 1) / vs_chunk_keys(N); }
 
 static int vs_slices(int N) { return (N + VS_SLICE - 1) / VS_SLICE; }
@@ -1704,8 +1706,10 @@ hipError_t launch_build_vs(const QKV &x, const HeadList &hl, int last_q, int nv,
                        (const float *)ml_fin, colsum, diagsum);
     return hipSuccess;
   };
-  const hipError_t e = vs_chunk_keys(N) == VS_CHUNK_SHORT ? score(std::integral_constant<int, VS_CHUNK_SHORT>{})
-                                                         : score(std::integral_constant<int, VS_CHUNK>{});
+  const int ck = vs_chunk_keys(N);
+  const hipError_t e = ck == VS_CHUNK_TINY    ? score(std::integral_constant<int, VS_CHUNK_TINY>{})
+                       : ck == VS_CHUNK_SHORT ? score(std::integral_constant<int, VS_CHUNK_SHORT>{})
+                                              : score(std::integral_constant<int, VS_CHUNK>{});
   if (e != hipSuccess) return e;
   // top-k of the line scores: prefilter by many workgroups, exact selection on what is left
   const int kv_ = nv < N ? nv : N, ks_ = ns < N ? ns : N;
