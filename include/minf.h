@@ -119,10 +119,11 @@ const char *minf_status_string(minf_status s);
 /* Number of 32-bit words per head of minf_vs_index.cover_bits. */
 int32_t minf_vs_cover_words(int32_t seq_len);
 
-/* Workspace sizes in bytes (0 on invalid arguments).  The Block-Sparse build needs the pooled
- * vectors only (512 bytes per head and 64-token block, Q and K) when topk <= 112 and the sequence
- * has fewer than 65536 blocks: block logits and selection are then fused and no logit is stored.
- * Larger budgets stage the logits of a few heads at a time: up to 2 GiB more. */
+/* Workspace sizes in bytes (0 on invalid arguments).  The Block-Sparse build needs the pooled K
+ * only (512 bytes per head and 64-token block) when topk <= 112 and the sequence has fewer than
+ * 65536 blocks: pooling of Q, block logits and selection are then fused and neither the pooled Q
+ * nor a logit is stored.  Larger budgets also keep the pooled Q and stage the logits of a few
+ * heads at a time: up to 2 GiB more. */
 size_t minf_vs_index_workspace_bytes(const minf_qkv *x, int32_t n_heads, int32_t last_q);
 size_t minf_bs_index_workspace_bytes(const minf_qkv *x, int32_t n_heads, int32_t topk);
 

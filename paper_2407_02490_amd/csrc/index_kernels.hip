@@ -1022,10 +1022,12 @@ __global__ __launch_bounds__(1024) void vs_lines_kernel(int N, int nv, int ns, c
 // ---------------------------------------------------------------------------
 // grid (NB, n_heads + n_kv): y < n_heads pools Q of head slot y, else K of kv[y - n_heads]
 // (the pooled K vectors of a K/V head are NBp >= NB rows apart: padded to whole 32-row tiles)
+// grid (NB, n_q + n_kv): n_q = the listed query heads, or 0 (qpool == nullptr) when the caller pools Q itself.
 __global__ __launch_bounds__(256) void bs_pool_kernel(QKV x, HeadList hl, KvMap km, float *qpool, float *kpool,
                                                       int NBp) {
   __shared__ float red[16][132];
-  const int b = blockIdx.x, y = blockIdx.y, NB = x.N / 64;
+  const int b = blockIdx.x, NB = x.N / 64;
+  const int y = qpool ? blockIdx.y : blockIdx.y + hl.n;
   const bf16_t *src;
   int64_t st;
   float *dst;
@@ -1448,15 +1450,37 @@ __device__ inline float bsf_bar_value(unsigned tau) {
   return __uint_as_float((tau & 0x80000000u) ? (tau & 0x7fffffffu) : ~tau);
 }
 
-__device__ __forceinline__ void bsf_load_q(const float *qp, float (&q)[32]) {
+// Q_hat[row][32 hq .. 32 hq + 31]: the mean of the block's 64 query rows, summed in the order of
+// bs_pool_kernel (tokens r, r + 16, r + 32, r + 48 first, then r = 0 .. 15), so that both give the same bits.
+__device__ __forceinline__ void bsf_pool_q(const bf16_t *q0, int64_t q_st, float (&q)[32]) {
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const float4 v = *reinterpret_cast<const float4 *>(qp + 4 * j);
-    q[4 * j] = v.x; q[4 * j + 1] = v.y; q[4 * j + 2] = v.z; q[4 * j + 3] = v.w;
+  for (int j = 0; j < 32; ++j) q[j] = 0.f;
+  for (int r = 0; r < 16; ++r) {
+    float part[32];
+#pragma unroll
+    for (int j = 0; j < 32; ++j) part[j] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const bf16_t *p = q0 + (int64_t)(r + 16 * i) * q_st;
+#pragma unroll
+      for (int c = 0; c < 4; ++c) {
+        const uint4 w = *reinterpret_cast<const uint4 *>(p + 8 * c);
+        const unsigned ww[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          part[8 * c + 2 * j] += __uint_as_float(ww[j] << 16);
+          part[8 * c + 2 * j + 1] += __uint_as_float(ww[j] & 0xffff0000u);
+        }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 32; ++j) q[j] += part[j];
   }
+#pragma unroll
+  for (int j = 0; j < 32; ++j) q[j] *= 1.0f / 64.0f;
 }
 
-__global__ __launch_bounds__(BSF_THREADS) void bs_topk_kernel(int NB, int NBp, int topk, KvMap km, const float *qpool,
+__global__ __launch_bounds__(BSF_THREADS) void bs_topk_kernel(QKV x, HeadList hl, int NB, int NBp, int topk, KvMap km,
                                                               const float *kpool, int32_t *blk_idx, int32_t *blk_cnt) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
   unsigned *ckey = reinterpret_cast<unsigned *>(lds + 2 * BSF_TILE_BYTES);
@@ -1475,11 +1499,10 @@ __global__ __launch_bounds__(BSF_THREADS) void bs_topk_kernel(int NB, int NBp, i
   float bar = bsf_bar_value(tau);                            // exceeds it.  Rows past the end take nothing.
 
   // B operand: Q_hat[row][32 hq + j], j = 0 .. 31 (the contraction index of the lane of quarter hq in
-  // MFMA step j is 32 hq + j, for both operands).  Read again after every cut of the lists: 32
-  // values that need not live through that call.
-  const float *qp = qpool + ((int64_t)slot * NB + min(row, NB - 1)) * 128 + 32 * hq;
+  // MFMA step j is 32 hq + j, for both operands), pooled here from the block's 64 query rows: the
+  // pooled Q never goes through memory.
   float q[32];
-  bsf_load_q(qp, q);
+  bsf_pool_q(x.q + hl.h[slot] * x.q_sh + (int64_t)(64 * min(row, NB - 1)) * x.q_st + 32 * hq, x.q_st, q);
   const float *kp = kpool + (int64_t)km.slot_kv[slot] * NBp * 128;
   const int last_row = min(R0 + BSF_ROWS, NB) - 1;           // last query block of the workgroup
   const int n_tiles = last_row / 32 + 1;                     // key tiles that hold a key <= last_row
@@ -1524,12 +1547,6 @@ __global__ __launch_bounds__(BSF_THREADS) void bs_topk_kernel(int NB, int NBp, i
     if (__builtin_amdgcn_ballot_w64(cnt + (int)(all & 255u) + (int)(all >> 8) > BSF_CAP)) {
       const BsfCut c = bsf_compact(keys, idx, cnt, k, false, hq, tau);
       cnt = c.cnt; tau = c.tau;
-      asm volatile("" ::: "memory");
-      bsf_load_q(qp, q);
-      // wait for them here (vmcnt 0, other counters untouched), in a form the compiler's own bookkeeping
-      // sees: otherwise every use of q in the tile loop waits on the memory counter, which also
-      // counts the tile load just issued, and the loop runs at the latency of that load
-      __builtin_amdgcn_s_waitcnt(0x0F70);
       bar = bsf_bar_value(tau);
 #pragma unroll
       for (int e = 0; e < 8; ++e)
@@ -1556,7 +1573,7 @@ __global__ __launch_bounds__(BSF_THREADS) void bs_topk_kernel(int NB, int NBp, i
 
   fetch(0);
   for (int t = 0; t < n_tiles; ++t) {
-    __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0), as an instruction the compiler's own counting sees (see below)
+    __builtin_amdgcn_s_waitcnt(0x0F70);                      // vmcnt(0), as an instruction the compiler's own wait counting sees
     __syncthreads();                                         // tile t landed; every wave is done with tile t-1
     if (t + 1 < n_tiles) fetch(t + 1);
     if (t > t_last) continue;                                // no key of the tile is causal for this wave
@@ -1755,10 +1772,11 @@ static bool bs_fused(int NB, int topk) { return topk <= BSF_MAX_TOPK && NB < 655
 size_t bs_index_ws_bytes(int N, int n_heads, int topk) {
   const int NB = N / 64;
   size_t b = 0;
-  b += align256((size_t)n_heads * NB * 128 * sizeof(float));                   // pooled Q
   b += align256((size_t)n_heads * bs_rows_padded(NB) * 128 * sizeof(float));   // pooled K, whole 32-row tiles
-  if (!bs_fused(NB, topk))
+  if (!bs_fused(NB, topk)) {
+    b += align256((size_t)n_heads * NB * 128 * sizeof(float));                 // pooled Q
     b += align256((size_t)bs_head_batch(NB, n_heads) * NB * NB * sizeof(float)); // block logits
+  }
   return b;
 }
 
@@ -1783,17 +1801,20 @@ hipError_t launch_build_bs(const QKV &x, const HeadList &hl, int topk, int32_t *
   for (int i = km.n_kv; i < MINF_MAX_HEADS; ++i) km.kv[i] = 0;
   const int NBp = bs_rows_padded(NB);
   char *p = static_cast<char *>(ws);
-  float *qpool = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * NB * 128 * sizeof(float));
+  const bool fused = bs_fused(NB, topk);
   float *kpool = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * NBp * 128 * sizeof(float));
+  float *qpool = nullptr;
+  if (!fused) { qpool = reinterpret_cast<float *>(p); p += align256((size_t)hl.n * NB * 128 * sizeof(float)); }
   float *scores = reinterpret_cast<float *>(p);
-  hipLaunchKernelGGL(bs_pool_kernel, dim3(NB, hl.n + km.n_kv), dim3(256), 0, st, x, hl, km, qpool, kpool, NBp);
-  if (bs_fused(NB, topk)) {
-    // block logits and top-k in one kernel: nothing of size NB x NB is stored
+  hipLaunchKernelGGL(bs_pool_kernel, dim3(NB, (fused ? 0 : hl.n) + km.n_kv), dim3(256), 0, st, x, hl, km, qpool, kpool,
+                     NBp);
+  if (fused) {
+    // pooling of Q, block logits and top-k in one kernel: neither the pooled Q nor anything of size NB x NB is stored
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs_topk_kernel),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)BSF_LDS);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(bs_topk_kernel, dim3(hl.n, (NB + BSF_ROWS - 1) / BSF_ROWS), dim3(BSF_THREADS), BSF_LDS, st, NB, NBp,
-                       topk, km, (const float *)qpool, (const float *)kpool, blk_idx, blk_cnt);
+    hipLaunchKernelGGL(bs_topk_kernel, dim3(hl.n, (NB + BSF_ROWS - 1) / BSF_ROWS), dim3(BSF_THREADS), BSF_LDS, st, x, hl,
+                       NB, NBp, topk, km, (const float *)kpool, blk_idx, blk_cnt);
   } else {
     // budgets beyond the candidate lists of the fused kernel: logits through memory, head batches
     const int hbmax = bs_head_batch(NB, hl.n);

@@ -80,22 +80,23 @@ def _qkv(N, n_q=32, n_kv=8):
 
 
 def test_workspace_sizes(lib):
-    """Host arithmetic only.  The Block-Sparse build stores no block logits up to a budget of 112 blocks
-    (Alg. 3's top-k is then fused with the logits): pooled Q and K alone, 512 bytes per head and block each."""
+    """Host arithmetic only.  Up to a budget of 112 blocks the Block-Sparse build stores neither block logits
+    nor the pooled Q (Alg. 3's pooling of Q and its top-k are then fused with the logits): the pooled K alone,
+    512 bytes per head and block."""
     lib.minf_bs_index_workspace_bytes.restype = ctypes.c_size_t
     lib.minf_vs_index_workspace_bytes.restype = ctypes.c_size_t
     x = _qkv(1 << 20)
     NB = (1 << 20) // 64
     fused = lib.minf_bs_index_workspace_bytes(ctypes.byref(x), 6, 100)
-    assert fused == 2 * 6 * NB * 512
+    assert fused == 6 * NB * 512
     assert lib.minf_bs_index_workspace_bytes(ctypes.byref(x), 6, 112) == fused
     staged = lib.minf_bs_index_workspace_bytes(ctypes.byref(x), 6, 113)
-    assert staged >= fused + 2 * NB * NB * 4                                            # at least two heads' logits
+    assert staged >= 2 * fused + 2 * NB * NB * 4                                        # pooled Q too, and at least two heads' logits
     assert lib.minf_bs_index_workspace_bytes(ctypes.byref(x), 6, 0) == 0
     assert lib.minf_bs_index_workspace_bytes(ctypes.byref(x), 0, 100) == 0
     # ragged number of blocks: pooled K is padded to whole 32-row tiles
     y = _qkv(64 * 33)
-    assert lib.minf_bs_index_workspace_bytes(ctypes.byref(y), 1, 8) == 33 * 512 + 64 * 512
+    assert lib.minf_bs_index_workspace_bytes(ctypes.byref(y), 1, 8) == 64 * 512
     # Vertical-Slash: grows with heads x tokens, within 16 .. 24 bytes per head and token
     per = lib.minf_vs_index_workspace_bytes(ctypes.byref(x), 24, 64) / (24 * (1 << 20))
     assert 16 <= per <= 24
