@@ -92,7 +92,8 @@ class Layer:
         if self.bs_heads:
             self.bs_idx = B.alloc_bs_index(len(self.bs_heads), self.N, c["topk"])
             self.bs_ws = u8(B.minf_bs_index_workspace_bytes(x.q, x.k, len(self.bs_heads), c["topk"]))
-        self.t = {k: Timer() for k in ("vs_index", "bs_index", "ashape_attn", "vs_attn", "bs_attn")}
+        self.t = {k: Timer() for k in ("vs_index", "bs_index", "ashape_attn", "vs_attn", "bs_attn", "vs_bs_attn")}
+        self.one_launch = False
 
     def step(self):
         x, c, t = self.x, self.cfg, self.t
@@ -106,6 +107,10 @@ class Layer:
         if self.a_heads:
             with t["ashape_attn"]:
                 B.minf_ashape_attn(x.q, x.k, x.v, self.o, self.a_heads, c["n_init"], c["n_local"])
+        if self.one_launch and self.vs_heads and self.bs_heads:
+            with t["vs_bs_attn"]:           # both patterns in one launch (measured alternative, --one-launch)
+                B.minf_vs_bs_attn(x.q, x.k, x.v, self.o, self.vs_heads, self.vs_idx, self.bs_heads, self.bs_idx)
+            return
         if self.vs_heads:
             with t["vs_attn"]:
                 B.minf_vs_attn(x.q, x.k, x.v, self.o, self.vs_heads, self.vs_idx)
@@ -162,6 +167,9 @@ class Layer:
         tiles = self.tiles()
         done = self.executed_tiles()
         nnz = self.nnz()
+        if self.one_launch and self.vs_heads and self.bs_heads:
+            for d in (tiles, done, nnz):
+                d["vs_bs_attn"] = d.pop("vs_attn") + d.pop("bs_attn")
         r = {"workload": self.name, "seq_len": self.N, "ms_per_layer": round(wall_ms, 4), "calls": {}}
         tot_tiles = tot_done = 0
         for k, t in self.t.items():
@@ -444,6 +452,9 @@ def main():
     ap.add_argument("--no-128k", action="store_true", help="skip the three 128K single-pattern layers")
     ap.add_argument("--no-dense", action="store_true", help="skip the dense causal baseline")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--one-launch", action="store_true",
+                    help="run the Vertical-Slash and the Block-Sparse heads of the layer in one launch "
+                         "(minf_vs_bs_attn: the measured, slower alternative) instead of two")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy (known HBM bytes) so that "
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE readings can be scaled")
@@ -498,6 +509,7 @@ def main():
 
     # ---- the timed workload
     L = Layer(a.workload)
+    L.one_launch = a.one_launch
     torch.cuda.synchronize()
     wall = L.run(a.steps, a.warmup)
     rep = L.report(wall)

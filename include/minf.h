@@ -218,6 +218,20 @@ minf_status minf_vs_attn(const minf_qkv *x, const int32_t *heads, int32_t n_head
 minf_status minf_bs_attn(const minf_qkv *x, const int32_t *heads, int32_t n_heads,
                          const minf_bs_index *idx, void *hip_stream);
 
+/*
+ * Vertical-Slash and Block-Sparse heads of one layer in a single launch (the
+ * layers of the paper's models mix the patterns: Section 3.2, App. E).  Same
+ * arguments, checks and results (bit for bit) as minf_vs_attn on vs_heads
+ * followed by minf_bs_attn on bs_heads; a head must not be in both lists
+ * (MINF_ERR_SHAPE).  The work items of the two patterns are interleaved four
+ * to one so that every part of the chip holds both kinds at once.  Measured
+ * slower than the two separate calls on the mixed 1M-token layer (the
+ * patterns disturb each other's cache reuse); provided as the measured
+ * alternative.
+ */
+minf_status minf_vs_bs_attn(const minf_qkv *x, const int32_t *vs_heads, int32_t n_vs, const minf_vs_index *vs,
+                            const int32_t *bs_heads, int32_t n_bs, const minf_bs_index *bs, void *hip_stream);
+
 /* Dense causal attention with the same kernels: the speedup baseline. */
 minf_status minf_dense_attn(const minf_qkv *x, const int32_t *heads, int32_t n_heads,
                             void *hip_stream);

@@ -13,7 +13,7 @@ import torch
 __all__ = [
     "lib", "MinfError", "VSIndex", "BSIndex", "alloc_vs_index", "alloc_bs_index",
     "vs_index_from_host", "bs_index_from_host",
-    "minf_build_vs_index", "minf_build_vs_index_noalloc", "minf_vs_index_from_lines", "minf_build_bs_index", "minf_ashape_attn", "minf_vs_attn",
+    "minf_build_vs_index", "minf_build_vs_index_noalloc", "minf_vs_index_from_lines", "minf_build_bs_index", "minf_ashape_attn", "minf_vs_attn", "minf_vs_bs_attn",
     "minf_bs_attn", "minf_dense_attn", "minf_vs_cover_words",
     "minf_vs_index_workspace_bytes", "minf_bs_index_workspace_bytes",
 ]
@@ -87,6 +87,8 @@ def lib():
     L.minf_vs_attn.argtypes = [pq, pi, i32, ctypes.POINTER(_VSIndex), vp]
     L.minf_bs_attn.restype = ctypes.c_int
     L.minf_bs_attn.argtypes = [pq, pi, i32, ctypes.POINTER(_BSIndex), vp]
+    L.minf_vs_bs_attn.restype = ctypes.c_int
+    L.minf_vs_bs_attn.argtypes = [pq, pi, i32, ctypes.POINTER(_VSIndex), pi, i32, ctypes.POINTER(_BSIndex), vp]
     _lib = L
     return L
 
@@ -289,3 +291,11 @@ def minf_bs_attn(q, k, v, o, heads, idx, scale=0.0, stream=None):
     h, n = _heads(heads)
     s = idx.c_struct()
     _check(lib().minf_bs_attn(ctypes.byref(x), h, n, ctypes.byref(s), _stream(stream)))
+
+
+def minf_vs_bs_attn(q, k, v, o, vs_heads, vs_idx, bs_heads, bs_idx, scale=0.0, stream=None):
+    x = _qkv(q, k, v, o, scale)
+    hv, nv = _heads(vs_heads)
+    hb, nb = _heads(bs_heads)
+    sv, sb = vs_idx.c_struct(), bs_idx.c_struct()
+    _check(lib().minf_vs_bs_attn(ctypes.byref(x), hv, nv, ctypes.byref(sv), hb, nb, ctypes.byref(sb), _stream(stream)))

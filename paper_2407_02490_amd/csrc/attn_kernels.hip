@@ -1631,14 +1631,12 @@ struct BsGen {
   }
 };
 
+// One work item = one wave: query block b (a position in the processing order, if there is one) of list slot `slot`.
 template <bool ROWS256>
-__global__ __launch_bounds__(64) void bs_kernel(QKV x, HeadList hl, const int32_t *blk_idx,
-                                                const int32_t *blk_cnt, const int32_t *order, int topk,
-                                                Sched sched) {
-  extern __shared__ __attribute__((aligned(1024))) char lds[];
+__device__ __forceinline__ void bs_item(const QKV &x, const HeadList &hl, const int32_t *blk_idx,
+                                        const int32_t *blk_cnt, const int32_t *order, int topk, int slot, int b,
+                                        char *lds) {
   const int NB = x.N / BQ;
-  int slot, b;
-  if (!decode_wg(sched, slot, b)) return;
   if (order) {
     // position in the processing order -> query block (a permutation: every block is taken once)
     b = __builtin_amdgcn_readfirstlane(order[(int64_t)slot * NB + b]);
@@ -1689,6 +1687,16 @@ __global__ __launch_bounds__(64) void bs_kernel(QKV x, HeadList hl, const int32_
     bs_pass<PASS_FIX>(c, st, lo, mp, lane);
   }
   wave_finish(st, oh, x.o_st, q0, lds, lane);
+}
+
+template <bool ROWS256>
+__global__ __launch_bounds__(64) void bs_kernel(QKV x, HeadList hl, const int32_t *blk_idx,
+                                                const int32_t *blk_cnt, const int32_t *order, int topk,
+                                                Sched sched) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  int slot, b;
+  if (!decode_wg(sched, slot, b)) return;
+  bs_item<ROWS256>(x, hl, blk_idx, blk_cnt, order, topk, slot, b, lds);
 }
 
 // ---------------------------------------------------------------------------
@@ -1905,15 +1913,12 @@ __device__ inline void vs_pass_pipelined(const VsCtx &c, WaveState &st, const La
   vs_cols_pipelined<ROWS256>(c, st, qa, has_ref, lo, mp, dk, dv, lane);
 }
 
+// One work item = one wave: query block b of list slot `slot`.
 template <bool ROWS256>
-__global__ __launch_bounds__(64) void vs_kernel(QKV x, HeadList hl, const int32_t *v_idx,
-                                                const int32_t *cover, const uint32_t *cover_bits,
-                                                const int32_t *counts, int nv, int ns, int cover_words,
-                                                Sched sched) {
-  extern __shared__ __attribute__((aligned(1024))) char lds[];
-  const int NB = x.N / BQ;
-  int slot, b;
-  if (!decode_wg(sched, slot, b)) return;
+__device__ __forceinline__ void vs_item(const QKV &x, const HeadList &hl, const int32_t *v_idx,
+                                        const int32_t *cover, const uint32_t *cover_bits,
+                                        const int32_t *counts, int nv, int ns, int cover_words, int slot, int b,
+                                        char *lds) {
   const int head = __builtin_amdgcn_readfirstlane(hl.h[slot]);
   const int kvh = to_sgpr(head / x.group);
   const bf16_t *qh = x.q + head * x.q_sh;
@@ -1948,6 +1953,51 @@ __global__ __launch_bounds__(64) void vs_kernel(QKV x, HeadList hl, const int32_
     vs_pass<PASS_FIX>(c, st, lo, mp, lane);
   }
   wave_finish(st, oh, x.o_st, q0, lds, lane);
+}
+
+template <bool ROWS256>
+__global__ __launch_bounds__(64) void vs_kernel(QKV x, HeadList hl, const int32_t *v_idx,
+                                                const int32_t *cover, const uint32_t *cover_bits,
+                                                const int32_t *counts, int nv, int ns, int cover_words,
+                                                Sched sched) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  int slot, b;
+  if (!decode_wg(sched, slot, b)) return;
+  vs_item<ROWS256>(x, hl, v_idx, cover, cover_bits, counts, nv, ns, cover_words, slot, b, lds);
+}
+
+// Vertical-Slash and Block-Sparse heads of a layer in ONE launch (the layers of the paper's models
+// mix the patterns, App. E): the work items of the two kinds are interleaved four to one in
+// launch order, each kind keeping its own XCD-aware mapping (a workgroup id's low three bits are
+// the XCD in both), so that every XCD holds both kinds at any time.  Same results as the two
+// separate launches, bit for bit; measured slower than them (the Block-Sparse items stream other
+// K/V heads through the L2s that the Vertical-Slash items share) and therefore not what
+// minf_vs_attn / minf_bs_attn do: kept as the measured alternative.
+struct VsArgs {
+  const int32_t *v_idx, *cover;
+  const uint32_t *cover_bits;
+  const int32_t *counts;
+  int nv, ns, cover_words;
+};
+struct BsArgs {
+  const int32_t *blk_idx, *blk_cnt, *order;
+  int topk;
+};
+template <bool ROWS256>
+__global__ __launch_bounds__(64) void vs_bs_kernel(QKV x, HeadList hv, VsArgs va, Sched sv, HeadList hb, BsArgs ba,
+                                                   Sched sb) {
+  extern __shared__ __attribute__((aligned(1024))) char lds[];
+  const int w = blockIdx.x, g = w / 40, r = w - 40 * g, xcd = r & 7, kind = r >> 3;   // kind 0 .. 3: VS, 4: BS
+  int slot, b;
+  if (kind < 4) {
+    const int hw = (4 * g + kind) * 8 + xcd;
+    if (hw >= 8 * sv.per_xcd || !decode_item(sv, hw, slot, b)) return;
+    vs_item<ROWS256>(x, hv, va.v_idx, va.cover, va.cover_bits, va.counts, va.nv, va.ns, va.cover_words, slot, b, lds);
+  } else {
+    const int hw = g * 8 + xcd;
+    if (hw >= 8 * sb.per_xcd || !decode_item(sb, hw, slot, b)) return;
+    bs_item<ROWS256>(x, hb, ba.blk_idx, ba.blk_cnt, ba.order, ba.topk, slot, b, lds);
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -2358,6 +2408,30 @@ hipError_t launch_vs(const QKV &x, const HeadList &hl, const int32_t *v_idx, con
   else
     hipLaunchKernelGGL(vs_kernel<false>, dim3(s.per_xcd * 8), dim3(64), lds, st, x, hl, v_idx, cover, cover_bits,
                        counts, nv, ns, cover_words, s);
+  return hipGetLastError();
+}
+
+hipError_t launch_vs_bs(const QKV &x, const HeadList &hv, const int32_t *v_idx, const int32_t *cover,
+                        const uint32_t *cover_bits, const int32_t *counts, int nv, int ns, int cover_words,
+                        const HeadList &hb, const int32_t *blk_idx, const int32_t *blk_cnt, const int32_t *order,
+                        int topk, hipStream_t st) {
+  const int NB = x.N / BQ;
+  const Sched sv = make_sched(hv, x.group, NB), sb = make_sched(hb, x.group, NB);
+  const VsArgs va{v_idx, cover, cover_bits, counts, nv, ns, cover_words};
+  const BsArgs ba{blk_idx, blk_cnt, order, topk};
+  const size_t lds = 5 * HALF_BYTES;
+  const bool rows256 = x.k_st == D && x.v_st == D;
+  const void *fn = rows256 ? reinterpret_cast<const void *>(vs_bs_kernel<true>)
+                           : reinterpret_cast<const void *>(vs_bs_kernel<false>);
+  hipError_t e = set_lds(fn, lds);
+  if (e != hipSuccess) return e;
+  // groups of 40 workgroup ids: 32 Vertical-Slash positions and 8 Block-Sparse positions
+  const int gv = (8 * sv.per_xcd + 31) / 32, gb = sb.per_xcd;
+  const int groups = gv > gb ? gv : gb;
+  if (rows256)
+    hipLaunchKernelGGL(vs_bs_kernel<true>, dim3(40 * groups), dim3(64), lds, st, x, hv, va, sv, hb, ba, sb);
+  else
+    hipLaunchKernelGGL(vs_bs_kernel<false>, dim3(40 * groups), dim3(64), lds, st, x, hv, va, sv, hb, ba, sb);
   return hipGetLastError();
 }
 

@@ -274,4 +274,36 @@ minf_status minf_bs_attn(const minf_qkv *x, const int32_t *heads, int32_t n_head
   return MINF_OK;
 }
 
+minf_status minf_vs_bs_attn(const minf_qkv *x, const int32_t *vs_heads, int32_t n_vs, const minf_vs_index *vs,
+                            const int32_t *bs_heads, int32_t n_bs, const minf_bs_index *bs, void *hip_stream) {
+  minf_status s = check_qkv(x, true);
+  if (s != MINF_OK) return s;
+  HeadList hv, hb;
+  if ((s = check_heads(x, vs_heads, n_vs, hv)) != MINF_OK) return s;
+  if ((s = check_heads(x, bs_heads, n_bs, hb)) != MINF_OK) return s;
+  if (!vs || !vs->v_idx || !vs->cover || !vs->cover_bits || !vs->counts) return MINF_ERR_NULL;
+  if (!bs || !bs->blk_idx || !bs->blk_cnt) return MINF_ERR_NULL;
+  if (vs->block != MINF_BLOCK || bs->block != MINF_BLOCK) return MINF_ERR_UNSUPPORTED;
+  if (vs->nv < 1 || vs->ns < 1 || bs->topk < 1) return MINF_ERR_BUDGET;
+  if (vs->cover_words < minf_vs_cover_words(x->seq_len)) return MINF_ERR_SHAPE;
+  if ((uint64_t)x->seq_len * (uint64_t)x->k_stride[2] * 2u >= (1ull << 32) ||
+      (uint64_t)x->seq_len * (uint64_t)x->v_stride[2] * 2u >= (1ull << 32))
+    return MINF_ERR_SHAPE;
+  // a head in both lists would be written by two work items
+  for (int i = 0; i < n_vs; ++i)
+    for (int j = 0; j < n_bs; ++j)
+      if (vs_heads[i] == bs_heads[j]) return MINF_ERR_SHAPE;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int64_t NB = x->seq_len / MINF_BLOCK;
+  for (int b = 0; b < x->batch; ++b) {
+    const int64_t rv = (int64_t)b * n_vs, rb = (int64_t)b * n_bs;
+    hipError_t e = launch_vs_bs(view(x, b), hv, vs->v_idx + rv * vs->nv, vs->cover + rv * vs->ns * 2,
+                                vs->cover_bits + rv * vs->cover_words, vs->counts + rv * 4, vs->nv, vs->ns,
+                                vs->cover_words, hb, bs->blk_idx + rb * NB * bs->topk, bs->blk_cnt + rb * NB,
+                                bs->order ? bs->order + rb * NB : nullptr, bs->topk, st);
+    if (e != hipSuccess) return MINF_ERR_HIP;
+  }
+  return MINF_OK;
+}
+
 }  // extern "C"

@@ -106,6 +106,11 @@ hipError_t launch_vs(const QKV &x, const HeadList &hl, const int32_t *v_idx, con
                      const uint32_t *cover_bits, const int32_t *counts, int nv, int ns,
                      int cover_words, hipStream_t st);
 
+hipError_t launch_vs_bs(const QKV &x, const HeadList &hv, const int32_t *v_idx, const int32_t *cover,
+                        const uint32_t *cover_bits, const int32_t *counts, int nv, int ns, int cover_words,
+                        const HeadList &hb, const int32_t *blk_idx, const int32_t *blk_cnt, const int32_t *order,
+                        int topk, hipStream_t st);
+
 // index launches (index_kernels.hip)
 size_t vs_index_ws_bytes(int N, int n_heads);
 size_t bs_index_ws_bytes(int N, int n_heads, int topk);

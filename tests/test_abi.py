@@ -48,6 +48,7 @@ def test_null_arguments_are_rejected_on_the_host(lib):
     assert lib.minf_dense_attn(None, None, 0, None) == 1
     assert lib.minf_vs_attn(None, None, 0, None, None) == 1
     assert lib.minf_bs_attn(None, None, 0, None, None) == 1
+    assert lib.minf_vs_bs_attn(None, None, 0, None, None, 0, None, None) == 1
 
 
 def test_vs_index_from_lines_rejects_bad_arguments_on_the_host(lib):

@@ -420,3 +420,41 @@ def test_exact_fallback_on_underflow(B):
     devb = B.bs_index_from_host(idx, cnt)
     o = run_heads(B.minf_bs_attn, q, k, v, [0], devb)
     assert_close_rows(o[0], O.bs_attention(to_f64(q[0]), to_f64(k[0]), to_f64(v[0]), idx[0], cnt[0]), "underflow BS")
+
+
+def test_vs_and_bs_heads_in_one_launch_match_the_two_calls_bit_for_bit(B):
+    """minf_vs_bs_attn (Section 3.2 / App. E: a layer mixes the patterns): the interleaved launch gives what
+    minf_vs_attn followed by minf_bs_attn give, and leaves the other heads alone; token-major layout too."""
+    N = 4096
+    for layout in ("head", "token"):
+        q, k, v = random_qkv(71, 8, 2, N)
+        if layout == "token":
+            def tm(t):
+                return t.transpose(0, 1).contiguous().transpose(0, 1)
+            q, k, v = tm(q), tm(k), tm(v)
+        vs_heads, bs_heads = [0, 1, 5], [2, 7]
+        vidx = B.alloc_vs_index(len(vs_heads), 48, 100, N)
+        ws = torch.empty(B.minf_vs_index_workspace_bytes(q, k, len(vs_heads), 64), dtype=torch.uint8, device="cuda")
+        B.minf_build_vs_index(q, k, vs_heads, 64, 48, 100, vidx, ws)
+        bidx = B.alloc_bs_index(len(bs_heads), N, 9)
+        ws2 = torch.empty(B.minf_bs_index_workspace_bytes(q, k, len(bs_heads), 9), dtype=torch.uint8, device="cuda")
+        B.minf_build_bs_index(q, k, bs_heads, 9, bidx, ws2)
+        o1 = torch.full_like(q, 7.0)
+        o2 = torch.full_like(q, 7.0)
+        B.minf_vs_attn(q, k, v, o1, vs_heads, vidx)
+        B.minf_bs_attn(q, k, v, o1, bs_heads, bidx)
+        B.minf_vs_bs_attn(q, k, v, o2, vs_heads, vidx, bs_heads, bidx)
+        torch.cuda.synchronize()
+        assert torch.equal(o1, o2), layout
+        assert bool((o2[[3, 4, 6]] == 7.0).all())
+        # against the oracle, one head of each kind
+        Vg, Sg = vidx.v_idx[1].cpu().numpy(), vidx.s_idx[1].cpu().numpy()
+        cnt = vidx.counts[1].cpu().numpy()
+        Qh, Kh, Vh = to_f64(q[1]), to_f64(k[0]), to_f64(v[0])
+        assert_close_rows(o2[1], O.vs_attention(Qh, Kh, Vh, Vg[:cnt[0]], Sg[:cnt[1]], Bm=64), f"one launch VS {layout}")
+        Qh, Kh, Vh = to_f64(q[7]), to_f64(k[1]), to_f64(v[1])
+        bi, bc = bidx.blk_idx[1].cpu().numpy(), bidx.blk_cnt[1].cpu().numpy()
+        assert_close_rows(o2[7], O.bs_attention(Qh, Kh, Vh, bi, bc, B=64), f"one launch BS {layout}")
+    with pytest.raises(B.MinfError) as e:
+        B.minf_vs_bs_attn(q, k, v, o2, [0, 1], vidx, [1], bidx)      # head 1 in both lists
+    assert e.value.status == 2
