@@ -1987,17 +1987,12 @@ template <bool ROWS256>
 __global__ __launch_bounds__(64) void vs_bs_kernel(QKV x, HeadList hv, VsArgs va, Sched sv, HeadList hb, BsArgs ba,
                                                    Sched sb) {
   extern __shared__ __attribute__((aligned(1024))) char lds[];
-  const int w = blockIdx.x, g = w / 40, r = w - 40 * g, xcd = r & 7, kind = r >> 3;   // kind 0 .. 3: VS, 4: BS
-  int slot, b;
-  if (kind < 4) {
-    const int hw = (4 * g + kind) * 8 + xcd;
-    if (hw >= 8 * sv.per_xcd || !decode_item(sv, hw, slot, b)) return;
+  int kind, slot, b;
+  if (!decode_mixed(sv, sb, blockIdx.x, kind, slot, b)) return;
+  if (kind == 0)
     vs_item<ROWS256>(x, hv, va.v_idx, va.cover, va.cover_bits, va.counts, va.nv, va.ns, va.cover_words, slot, b, lds);
-  } else {
-    const int hw = g * 8 + xcd;
-    if (hw >= 8 * sb.per_xcd || !decode_item(sb, hw, slot, b)) return;
+  else
     bs_item<ROWS256>(x, hb, ba.blk_idx, ba.blk_cnt, ba.order, ba.topk, slot, b, lds);
-  }
 }
 
 // ---------------------------------------------------------------------------
@@ -2426,8 +2421,7 @@ hipError_t launch_vs_bs(const QKV &x, const HeadList &hv, const int32_t *v_idx, 
   hipError_t e = set_lds(fn, lds);
   if (e != hipSuccess) return e;
   // groups of 40 workgroup ids: 32 Vertical-Slash positions and 8 Block-Sparse positions
-  const int gv = (8 * sv.per_xcd + 31) / 32, gb = sb.per_xcd;
-  const int groups = gv > gb ? gv : gb;
+  const int groups = mixed_groups(sv, sb);
   if (rows256)
     hipLaunchKernelGGL(vs_bs_kernel<true>, dim3(40 * groups), dim3(64), lds, st, x, hv, va, sv, hb, ba, sb);
   else

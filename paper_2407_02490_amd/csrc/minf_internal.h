@@ -93,6 +93,21 @@ __host__ __device__ inline bool decode_item(const Sched &s, int hw, int &slot, i
   blk = s.n_blk - 1 - rank;
   return rank < s.n_blk;
 }
+// Two launches in one (Vertical-Slash and Block-Sparse heads of a layer): workgroup ids come in groups of
+// 40 = 32 positions of the first launch order and 8 of the second, so that the two kinds are interleaved
+// four to one and a position's low three bits stay the XCD of the hardware id.  kind 0: first, 1: second.
+// Returns false if the id holds no item.  groups = max(ceil(8 a.per_xcd / 32), b.per_xcd), grid = 40 groups.
+__host__ __device__ inline int mixed_groups(const Sched &a, const Sched &b) {
+  const int ga = (8 * a.per_xcd + 31) / 32;
+  return ga > b.per_xcd ? ga : b.per_xcd;
+}
+__host__ __device__ inline bool decode_mixed(const Sched &a, const Sched &b, int w, int &kind, int &slot, int &blk) {
+  const int g = w / 40, r = w - 40 * g, xcd = r & 7, q = r >> 3;
+  kind = q < 4 ? 0 : 1;
+  const Sched &s = kind == 0 ? a : b;
+  const int hw = kind == 0 ? (4 * g + q) * 8 + xcd : g * 8 + xcd;
+  return hw < 8 * s.per_xcd && decode_item(s, hw, slot, blk);
+}
 // Returns false if this workgroup has no work item.
 __device__ inline bool decode_wg(const Sched &s, int &slot, int &blk) {
   return decode_item(s, blockIdx.x, slot, blk);

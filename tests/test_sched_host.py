@@ -19,7 +19,7 @@ def test_every_work_item_is_mapped_exactly_once():
         assert r.returncode == 0, r.stderr[-2000:]
         r = subprocess.run([exe], capture_output=True, text=True)
         assert r.returncode == 0, r.stdout[-2000:] + r.stderr[-2000:]
-        assert "FAIL" not in r.stdout and r.stdout.count("ok heads") == 57
+        assert "FAIL" not in r.stdout and r.stdout.count("ok heads") == 57 and r.stdout.count("ok mixed") == 15
 
 
 def test_shared_tile_vertical_slash_schedule_covers_every_run_key_once():
