@@ -371,6 +371,22 @@ def test_batch_of_two_all_calls(B):
             Qh, Kh, Vh = to_f64(q[b, h]), to_f64(k[b, h // 2]), to_f64(v[b, h // 2])
             got, cnt, _ = check_bs_index(bidx, b * len(heads) + j, Qh, Kh, topk)
             assert_close_rows(o[b, h], O.bs_attention(Qh, Kh, Vh, got, cnt), f"batch {b} bs head {h}")
+    # both patterns in one launch: Vertical-Slash on head 1 (rows 0 and 2 of idx), Block-Sparse on head 2
+    # (rows 1 and 3 of bidx) would not line up with two-head indices, so build one-head indices
+    vidx1 = B.alloc_vs_index(nb, nv, ns, N)
+    ws = torch.empty(B.minf_vs_index_workspace_bytes(q, k, 1, 64), dtype=torch.uint8, device="cuda")
+    B.minf_build_vs_index(q, k, [1], 64, nv, ns, vidx1, ws)
+    bidx1 = B.alloc_bs_index(nb, N, topk)
+    ws = torch.empty(B.minf_bs_index_workspace_bytes(q, k, 1, topk), dtype=torch.uint8, device="cuda")
+    B.minf_build_bs_index(q, k, [2], topk, bidx1, ws)
+    o_two = torch.full_like(q, float("nan"))
+    o_one = torch.full_like(q, float("nan"))
+    B.minf_vs_attn(q, k, v, o_two, [1], vidx1)
+    B.minf_bs_attn(q, k, v, o_two, [2], bidx1)
+    B.minf_vs_bs_attn(q, k, v, o_one, [1], vidx1, [2], bidx1)
+    torch.cuda.synchronize()
+    assert torch.equal(o_one[:, 1:3], o_two[:, 1:3])
+    assert torch.isnan(o_one[:, 0].float()).all() and torch.isnan(o_one[:, 3].float()).all()
     # A-shape and dense
     o = torch.full_like(q, float("nan"))
     B.minf_ashape_attn(q, k, v, o, [0], 64, 200)
