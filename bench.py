@@ -422,7 +422,11 @@ def roofline_of(rep, workload):
     return {"bound": "mfma", "kernel": dom, "achieved": d["tflops"], "peak": PEAK_BF16_TFLOPS,
             "unit": "TFLOP/s", "frac": round(d["tflops"] / PEAK_BF16_TFLOPS, 4),
             "traffic": read_traffic(f"{dom}:{workload}"),
-            "flops_per_launch": d["executed_tiles"] * FT, "avg_launch_ms": d["ms"]}
+            "flops_per_launch": d["executed_tiles"] * FT, "avg_launch_ms": d["ms"],
+            # the same launch priced by the canonical 64 x 64 tiles of its mask (the unit earlier
+            # versions of this line used; higher for Vertical-Slash, whose steps are 32 keys wide)
+            "achieved_canonical_tiles": d["tflops_of_canonical_tiles"],
+            "frac_canonical_tiles": round(d["tflops_of_canonical_tiles"] / PEAK_BF16_TFLOPS, 4)}
 
 
 def read_traffic(kernel_tag):
